@@ -1,0 +1,87 @@
+"""Type2 storage formats of the slices (oracle side; test infrastructure).
+
+The paper stores each slice in the input format of the matrix unit ("Type2", Section 3):
+FP8 E4M3 or FP16 (Section 4.1).  The conversion cvt_Type2 of Eq. 8 is exact by
+construction of the slices, so "encoding" here means: find the code whose value IS the
+given number, and fail loudly if there is none.
+
+FP8 E4M3 follows the OCP 8-bit floating point definition (1 sign, 4 exponent bits with
+bias 7, 3 fraction bits, no infinities, S.1111.111 is NaN, largest finite value 448),
+which is the flavour the gfx950 matrix unit consumes.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+#: significand bits including the hidden bit (the paper's m_Type2, Section 3)
+SIGNIFICAND_BITS = {"fp8": 4, "fp16": 11, "fp6_e3m2": 3}
+
+
+def e4m3_decode_table() -> np.ndarray:
+    """Value of each of the 256 OCP E4M3 byte codes (NaN codes -> nan)."""
+    vals = np.empty(256, dtype=np.float64)
+    for code in range(256):
+        sign = -1.0 if code & 0x80 else 1.0
+        e = (code >> 3) & 0xF
+        f = code & 0x7
+        if e == 0xF and f == 0x7:
+            vals[code] = np.nan
+        elif e == 0:
+            vals[code] = sign * (f / 8.0) * 2.0 ** (1 - 7)          # subnormal
+        else:
+            vals[code] = sign * (1.0 + f / 8.0) * 2.0 ** (e - 7)    # normal
+    return vals
+
+
+_E4M3_VALUES = e4m3_decode_table()
+
+
+def e4m3_decode(codes: np.ndarray) -> np.ndarray:
+    return _E4M3_VALUES[np.asarray(codes, dtype=np.uint8)]
+
+
+def e4m3_encode_exact(values: np.ndarray) -> np.ndarray:
+    """Byte codes of `values`; every value must be exactly representable.  Zero (of either
+    sign) encodes as 0x00: the scheme never distinguishes the sign of a zero slice entry."""
+    values = np.asarray(values, dtype=np.float64)
+    finite_codes = np.array([c for c in range(256) if not np.isnan(_E4M3_VALUES[c]) and c != 0x80], dtype=np.uint8)
+    table_vals = _E4M3_VALUES[finite_codes]
+    order = np.argsort(table_vals, kind="stable")
+    sorted_vals = table_vals[order]
+    sorted_codes = finite_codes[order]
+    pos = np.searchsorted(sorted_vals, values.ravel())
+    pos = np.clip(pos, 0, len(sorted_vals) - 1)
+    if not np.array_equal(sorted_vals[pos], values.ravel()):
+        bad = values.ravel()[sorted_vals[pos] != values.ravel()]
+        raise ValueError(f"value not representable in FP8 E4M3: {bad[:4]}")
+    return sorted_codes[pos].reshape(values.shape)
+
+
+def fp16_encode_exact(values: np.ndarray) -> np.ndarray:
+    """IEEE binary16 bit patterns (uint16) of `values`; every value must be exactly representable."""
+    values = np.asarray(values, dtype=np.float64)
+    h = values.astype(np.float16)
+    if not np.array_equal(h.astype(np.float64), values):
+        raise ValueError("value not representable in FP16")
+    h = np.where(h == 0, np.float16(0.0), h)      # +0 for either zero
+    return h.view(np.uint16)
+
+
+def fp16_decode(codes: np.ndarray) -> np.ndarray:
+    return np.asarray(codes, dtype=np.uint16).view(np.float16).astype(np.float64)
+
+
+def encode_exact(fmt: str, values: np.ndarray) -> np.ndarray:
+    if fmt == "fp8":
+        return e4m3_encode_exact(values)
+    if fmt == "fp16":
+        return fp16_encode_exact(values)
+    raise ValueError(fmt)
+
+
+def decode(fmt: str, codes: np.ndarray) -> np.ndarray:
+    if fmt == "fp8":
+        return e4m3_decode(codes)
+    if fmt == "fp16":
+        return fp16_decode(codes)
+    raise ValueError(fmt)

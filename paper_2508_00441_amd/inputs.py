@@ -1,0 +1,59 @@
+"""Seeded synthetic input generators shared by the tests, the benchmark and the oracle checks.
+
+This module holds no arithmetic of the Ozaki scheme: it only draws matrices.
+
+The recipe is the phi-parametrised test matrix used in the Ozaki-scheme literature,
+    a = (u - 0.5) * exp(phi * z),   u ~ U(0,1),  z ~ N(0,1),
+which gives zero-mean entries whose magnitudes are log-normally spread; a larger phi
+widens the exponent range inside every row/column and therefore raises the number of
+slices the scheme needs.  The paper's own evaluation (Section 5.1) uses U(1,10) instead;
+`uniform_1_10` provides that recipe for the Table 2 style experiments.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def phi_matrix(rows: int, cols: int, phi: float, rng: np.random.Generator) -> np.ndarray:
+    """rows x cols float64 matrix (C order) with entries (u-0.5)*exp(phi*z)."""
+    u = rng.random((rows, cols))
+    z = rng.standard_normal((rows, cols))
+    z *= phi
+    np.exp(z, out=z)
+    u -= 0.5
+    u *= z
+    return u
+
+
+def phi_pair(m: int, n: int, k: int, phi: float, seed: int = 0):
+    """A (m x k) and B (k x n) drawn in that order from numpy.random.default_rng(seed)."""
+    rng = np.random.default_rng(seed)
+    A = phi_matrix(m, k, phi, rng)
+    B = phi_matrix(k, n, phi, rng)
+    return A, B
+
+
+def uniform_1_10(rows: int, cols: int, rng: np.random.Generator) -> np.ndarray:
+    """Entries uniform in (1, 10): the input of the paper's Section 5.1."""
+    return 1.0 + 9.0 * rng.random((rows, cols))
+
+
+def full_mantissa_one_binade(rows: int, cols: int, rng: np.random.Generator) -> np.ndarray:
+    """Entries in [1, 2) whose 52 fraction bits are random with the last bit forced to 1:
+    every one of the 53 significand bits carries information (the premise of Table 2)."""
+    frac = rng.integers(0, 1 << 52, size=(rows, cols), dtype=np.uint64) | np.uint64(1)
+    bits = frac | np.uint64(0x3FF0000000000000)
+    return bits.view(np.float64)
+
+
+#: The benchmark configurations: name -> shape, phi, slice format, k_block (0 = no blocking), accumulation mode.
+CONFIGS = {
+    "c1_256_fp8_hw":        dict(m=256,   n=256,   k=256,   phi=0.5, fmt="fp8",  k_block=0,    accum="hw"),
+    "c2_4096_fp8_hw":       dict(m=4096,  n=4096,  k=4096,  phi=1.0, fmt="fp8",  k_block=0,    accum="hw"),
+    "c3_8192_fp8_emu":      dict(m=8192,  n=8192,  k=8192,  phi=4.0, fmt="fp8",  k_block=0,    accum="emu"),
+    "c4_16384_fp16_kb1024": dict(m=16384, n=16384, k=16384, phi=1.0, fmt="fp16", k_block=1024, accum="hw"),
+    "c4_16384_fp16_kb4096": dict(m=16384, n=16384, k=16384, phi=1.0, fmt="fp16", k_block=4096, accum="hw"),
+    "c4_16384_fp8":         dict(m=16384, n=16384, k=16384, phi=1.0, fmt="fp8",  k_block=0,    accum="hw"),
+    "c5a_16384x1024_fp8":   dict(m=16384, n=16384, k=1024,  phi=2.0, fmt="fp8",  k_block=1024, accum="emu"),
+    "c5b_1024x65536_fp8":   dict(m=1024,  n=1024,  k=65536, phi=2.0, fmt="fp8",  k_block=8192, accum="emu"),
+}

@@ -1,0 +1,383 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU needed).
+
+Each test names the passage it pins.  None of them re-types the oracle's own formula:
+they use values the paper prints (Table 2, Section 5.4), exact rational arithmetic,
+the host FPU, an independent library conversion (torch's float8_e4m3fn) or closed forms.
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import exact, formats, ozaki_oracle as oz, softfloat
+from paper_2508_00441_amd import inputs
+
+
+# ------------------------------------------------------------------ Table 2 (Section 4.1)
+def _read_table2(golden_dir):
+    rows = []
+    with open(os.path.join(golden_dir, "table2_min_gemms.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            parts = line.split()
+            rows.append((int(parts[0]), [None if p == "--" else int(p) for p in parts[1:]]))
+    assert len(rows) == 16
+    return rows
+
+
+# columns of Table 2: (m_Type2, m_Type3)
+_T2_COLUMNS = [(11, 24), (11, 11), (4, 24), (4, 11), (3, 24), (3, 11)]
+
+
+def test_table2_all_cells_from_eq_1_to_3(golden_dir):
+    for k, cells in _read_table2(golden_dir):
+        for (m2, m3), printed in zip(_T2_COLUMNS, cells):
+            s = oz.table2_slice_count(k, m2, m3)
+            assert (None if s is None else s * s) == printed, (k, m2, m3)
+
+
+@pytest.mark.parametrize("col", [0, 2, 4])
+def test_table2_fp32_accumulate_columns_by_actually_slicing(golden_dir, col):
+    """Slice full-mantissa one-binade vectors of length k until the remainder is zero and count."""
+    m2, m3 = _T2_COLUMNS[col]
+    rng = np.random.default_rng(7)
+    for k, cells in _read_table2(golden_dir):
+        rho = oz.rho_const(k, m2, m3)
+        rows = 4 if k <= 16384 else 1
+        X = inputs.full_mantissa_one_binade(rows, k, rng)
+        X[:, ::2] *= -1.0
+        sl, cs = oz.slice_to_exhaustion(X, rho)
+        assert len(sl) ** 2 == cells[col], (k, len(sl))
+
+
+def test_section_5_4_gemm_counts(golden_dir):
+    want = {}
+    with open(os.path.join(golden_dir, "kbk_gemm_counts.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                kbk, g = line.split()
+                want[int(kbk)] = int(g)
+    assert want == {1024: 49, 4096: 64, 16384: 81}
+    for kbk, g in want.items():
+        assert oz.table2_slice_count(kbk, 11, 24) ** 2 == g
+    # "121/81" at k = 8192
+    assert oz.table2_slice_count(8192, 4, 24) ** 2 == 121 and oz.table2_slice_count(8192, 11, 24) ** 2 == 81
+
+
+def test_gamma_matches_the_printed_formula_in_floating_point():
+    for lk in range(0, 25):
+        k = 1 << lk
+        for m3 in (24, 11):
+            assert oz.gamma_const(k, m3) == math.ceil(53 - (m3 - math.log2(k)) / 2)
+    # between powers of two the integer form is the exact evaluation of the same expression
+    for k in (3, 5, 1000, 1023, 1025, 5000, 65535, 65537, 100000):
+        assert oz.gamma_const(k) == math.ceil(53 - (24 - math.log2(k)) / 2)
+
+
+def test_plan_bits_per_slice():
+    # largest b <= m2 with k_b * 4^b <= 2^24
+    for k, b in [(16, 4), (8192, 4), (65536, 4), (65537, 3), (262144, 3), (262145, 2)]:
+        assert oz.make_plan(k, "fp8").b == b
+    for k, b in [(16, 10), (17, 9), (64, 9), (256, 8), (1024, 7), (4096, 6), (16384, 5), (65536, 4)]:
+        assert oz.make_plan(k, "fp16").b == b
+    p = oz.make_plan(16384, "fp16", 1024)
+    assert (p.b, p.num_blocks, p.k_block) == (7, 16, 1024)
+    p = oz.make_plan(1000, "fp8", 384)
+    assert (p.num_blocks, p.k_block) == (3, 384)
+    with pytest.raises(ValueError):
+        oz.make_plan(1 << 25, "fp8")        # k * 4^0 > 2^24: not even one sign digit is exact
+
+
+# ------------------------------------------------------------------ Eq. 4-9: the split is error-free
+def _nasty_rows(rng, rows, k):
+    X = inputs.phi_matrix(rows, k, 3.0, rng)
+    X[0, :] = 0.0                                     # zero vector: c := 0
+    X[1, :] = 1.0                                     # max is a power of two
+    X[2, :] = np.nextafter(1.0, 2.0)                  # just above a power of two
+    X[3, :] = np.ldexp(rng.integers(-16, 17, k).astype(np.float64), -3)   # one-slice row
+    X[4, : k // 2] = 0.0
+    X[5, 0] = 2.0 ** 300
+    X[6, :] = inputs.full_mantissa_one_binade(1, k, rng)[0] * np.where(rng.random(k) < 0.5, -1, 1)
+    X[7, :] *= 2.0 ** -400
+    # ties: entries exactly half way between two slice values of the first slice
+    X[8, :] = 0.0
+    X[8, 0] = 1.0
+    X[8, 1:9] = (2 * np.arange(8) + 1) / 32.0         # odd multiples of 2^-5 when the first ulp is 2^-4
+    return X
+
+
+@pytest.mark.parametrize("fmt,k", [("fp8", 64), ("fp16", 64), ("fp16", 1024), ("fp8", 4096)])
+def test_slices_sum_back_exactly_and_fit_their_format(fmt, k):
+    rng = np.random.default_rng(11)
+    X = _nasty_rows(rng, 12, k)
+    plan = oz.make_plan(k, fmt)
+    s = 9
+    sl, cs, rem = oz.slice_rows(X, plan.rho, s)
+    b = plan.b
+    for p in range(s):
+        q = np.ldexp(sl[p], b)
+        assert np.array_equal(q, np.rint(q))                      # integer multiples of 2^-b
+        assert np.max(np.abs(q)) <= 2 ** b                        # inside [-1, 1]
+        codes = formats.encode_exact(fmt, sl[p])                  # representable in Type2 ...
+        assert np.array_equal(formats.decode(fmt, codes), sl[p])  # ... and round-trips
+    # remainder after slice p is at most half an ulp of that slice
+    sl1, cs1, rem1 = oz.slice_rows(X, plan.rho, 1)
+    assert np.all(np.abs(rem1) <= np.ldexp(1.0, cs1[0] - b - 1)[:, None])
+    # Eq. 9 in exact rational arithmetic, element by element (sampled columns to keep it quick)
+    cols = rng.choice(k, size=min(k, 24), replace=False)
+    for i in range(X.shape[0]):
+        for j in cols:
+            total = Fraction(float(rem[i, j]))
+            for p in range(s):
+                total += Fraction(float(sl[p][i, j])) * Fraction(2) ** int(cs[p][i])
+            assert total == Fraction(float(X[i, j])), (i, j)
+
+
+def test_exponent_rule_of_eq_4():
+    mx = np.array([0.0, 1.0, np.nextafter(1.0, 2.0), np.nextafter(1.0, 0.0), 3.0, 4.0, 2.0 ** -1074, 0.75])
+    assert list(oz.ceil_log2_exact(mx)) == [0, 0, 1, 0, 2, 2, -1074, 0]
+    # away from powers of two the printed ceil(log2(.)) agrees
+    rng = np.random.default_rng(3)
+    v = np.exp(rng.normal(0, 20, 2000))
+    frac = np.abs(np.log2(v) - np.rint(np.log2(v)))
+    keep = frac > 1e-9
+    assert np.array_equal(oz.ceil_log2_exact(v[keep]), np.ceil(np.log2(v[keep])).astype(np.int64))
+
+
+def test_rounding_is_to_nearest_even_integer_multiple():
+    """(x + sigma) - sigma must be x rounded to the nearest multiple of 2^(c-b), ties to even."""
+    k = 64
+    plan = oz.make_plan(k, "fp8")
+    X = _nasty_rows(np.random.default_rng(5), 12, k)
+    sl, cs, _ = oz.slice_rows(X, plan.rho, 1)
+    for i in range(X.shape[0]):
+        ulp = Fraction(2) ** int(cs[0][i] - plan.b)
+        for j in range(k):
+            t = Fraction(float(X[i, j])) / ulp
+            fl = math.floor(t)
+            diff = t - fl
+            if diff > Fraction(1, 2) or (diff == Fraction(1, 2) and fl % 2 == 1):
+                fl += 1
+            assert Fraction(float(sl[0][i, j])) * Fraction(2) ** plan.b == fl, (i, j)
+
+
+def test_e4m3_table_matches_torch_float8():
+    torch = pytest.importorskip("torch")
+    codes = np.arange(256, dtype=np.uint8)
+    mine = formats.e4m3_decode(codes)
+    theirs = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    both_nan = np.isnan(mine) & np.isnan(theirs)
+    assert np.array_equal(mine[~both_nan], theirs[~both_nan]) and both_nan.sum() == 2
+    # every slice value q/16 encodes to the byte torch produces
+    vals = np.arange(-16, 17) / 16.0
+    enc = formats.e4m3_encode_exact(vals)
+    ref = torch.from_numpy(vals).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    ref = np.where(vals == 0, 0, ref)
+    assert np.array_equal(enc, ref)
+    with pytest.raises(ValueError):
+        formats.e4m3_encode_exact(np.array([17 / 16.0]))
+
+
+# ------------------------------------------------------------------ Eq. 10-11
+def _exact_sum_of_terms(blocks, b):
+    """sum over blocks and pairs of 2^(cA+cB-2b) * P in exact rational arithmetic."""
+    m, n = blocks[0].S.shape
+    tot = [[Fraction(0) for _ in range(n)] for _ in range(m)]
+    for br in blocks:
+        for (p, q), P in zip(br.pairs, br.products):
+            for i in range(m):
+                for j in range(n):
+                    if P[i, j]:
+                        tot[i][j] += Fraction(int(P[i, j])) * Fraction(2) ** int(br.c_a[p - 1][i] + br.c_b[q - 1][j] - 2 * b)
+    return tot
+
+
+@pytest.mark.parametrize("fmt,kblock", [("fp8", 0), ("fp16", 0), ("fp8", 16), ("fp16", 10)])
+def test_all_slices_all_pairs_equal_the_exact_product(fmt, kblock):
+    """Eq. 10 with every slice and every pair is an identity: brute force on tiny, non-square inputs."""
+    rng = np.random.default_rng(21)
+    m, n, k = 5, 3, 37
+    A = inputs.phi_matrix(m, k, 2.0, rng)
+    B = inputs.phi_matrix(k, n, 2.0, rng)
+    A[1, 4] = 0.0
+    plan = oz.make_plan(k, fmt, kblock)
+    s_full = 0
+    for t in range(plan.num_blocks):
+        k0, k1 = t * plan.k_block, min(k, (t + 1) * plan.k_block)
+        s_full = max(s_full, len(oz.slice_to_exhaustion(A[:, k0:k1], plan.rho)[0]),
+                     len(oz.slice_to_exhaustion(B[k0:k1, :].T.copy(), plan.rho)[0]))
+    C, blocks = oz.ozaki_dgemm(A, B, fmt, s_full, kblock, mode="full", return_blocks=True)
+    tot = _exact_sum_of_terms(blocks, plan.b)
+    ref = exact.exact_matmul(A, B)
+    for i in range(m):
+        for j in range(n):
+            assert tot[i][j] == ref[i][j], (i, j)
+    # and the FP64-accumulated result is as good as a plain FP64 GEMM (Section 5.3)
+    for i in range(m):
+        for j in range(n):
+            scale = exact.exact_dot(A[i, :], B[:, j], absolute=True)
+            assert abs(Fraction(float(C[i, j])) - ref[i][j]) <= scale * Fraction(4 * k, 2 ** 53)
+
+
+def test_pair_products_stay_inside_the_exact_fp32_window():
+    """Eq. 11 at its edge: k = 65536 entries all equal to the row maximum -> q = 2^b everywhere."""
+    k = 65536
+    A = np.ones((2, k))
+    B = np.ones((k, 2))
+    B[:, 1] = -1.0
+    C, blocks = oz.ozaki_dgemm(A, B, "fp8", 1, 0, return_blocks=True)
+    P = blocks[0].products[0]
+    assert np.array_equal(np.abs(P), np.full((2, 2), 1 << 24))
+    assert np.array_equal(np.float32(P).astype(np.int64), P)       # representable in FP32
+    assert np.array_equal(C, A @ B)
+    # k-blocking keeps FP16 slices inside the window as well
+    k = 4096
+    C, blocks = oz.ozaki_dgemm(np.ones((1, k)), np.ones((k, 1)), "fp16", 1, 1024, return_blocks=True)
+    assert all(int(br.products[0][0, 0]) == 1 << 24 for br in blocks) and C[0, 0] == k
+
+
+def test_integer_rows_need_one_slice_and_give_the_textbook_integer_product():
+    rng = np.random.default_rng(2)
+    m, n, k = 9, 7, 48
+    QA = rng.integers(-16, 17, (m, k))
+    QB = rng.integers(-16, 17, (k, n))
+    QA[:, 0] = 16
+    QB[0, :] = -16                                             # make every row/column maximum exactly 2^4
+    ea = rng.integers(-30, 30, m)
+    eb = rng.integers(-30, 30, n)
+    A = np.ldexp(QA.astype(np.float64), ea[:, None])
+    B = np.ldexp(QB.astype(np.float64), eb[None, :])
+    C, blocks = oz.ozaki_dgemm(A, B, "fp8", 1, 0, return_blocks=True)
+    assert np.array_equal(blocks[0].products[0], QA @ QB)
+    assert np.array_equal(C, np.ldexp((QA @ QB).astype(np.float64), ea[:, None] + eb[None, :]))
+
+
+def test_scaling_and_permutation_invariants():
+    rng = np.random.default_rng(9)
+    m, n, k = 6, 5, 40
+    A = inputs.phi_matrix(m, k, 1.0, rng)
+    B = inputs.phi_matrix(k, n, 1.0, rng)
+    s = 6
+    C, blk = oz.ozaki_dgemm(A, B, "fp8", s, 0, return_blocks=True)
+    # scaling a row of A by 2^t shifts its exponents by t, leaves the slices alone, scales that row of C
+    A2 = A.copy()
+    A2[2, :] *= 2.0 ** 13
+    C2, blk2 = oz.ozaki_dgemm(A2, B, "fp8", s, 0, return_blocks=True)
+    for p in range(s):
+        assert np.array_equal(blk2[0].slices_a[p], blk[0].slices_a[p])
+        d = blk2[0].c_a[p] - blk[0].c_a[p]
+        assert d[2] == 13 and np.all(np.delete(d, 2) == 0)
+    C_expect = C.copy()
+    C_expect[2, :] *= 2.0 ** 13
+    assert np.array_equal(C2, C_expect)
+    # permuting the inner index leaves every pair product and C unchanged
+    perm = rng.permutation(k)
+    C3, blk3 = oz.ozaki_dgemm(A[:, perm], B[perm, :], "fp8", s, 0, return_blocks=True)
+    assert all(np.array_equal(x, y) for x, y in zip(blk3[0].products, blk[0].products))
+    assert np.array_equal(C3, C)
+    # (A B)^T = B^T A^T: transposed roles give the transposed pair products
+    C4, blk4 = oz.ozaki_dgemm(B.T.copy(), A.T.copy(), "fp8", s, 0, return_blocks=True)
+    pairs = blk[0].pairs
+    for (p, q), P in zip(pairs, blk[0].products):
+        P4 = blk4[0].products[blk4[0].pairs.index((q, p))]
+        assert np.array_equal(P4, P.T)
+
+
+def test_pair_order_is_least_significant_first():
+    assert oz.pair_order(3) == [(1, 3), (2, 2), (3, 1), (1, 2), (2, 1), (1, 1)]
+    assert len(oz.pair_order(16)) == 16 * 17 // 2
+    full = oz.pair_order(3, "full")
+    assert len(full) == 9 and full[0] == (3, 3) and full[-1] == (1, 1)
+
+
+# ------------------------------------------------------------------ accuracy (Section 5.3)
+def test_error_bound_and_decay_per_slice_on_the_small_config():
+    m = n = k = 256
+    A, B = inputs.phi_pair(m, n, k, 0.5, seed=0)
+    ent = exact.sample_entries(m, n, 24, seed=5)
+    rows = sorted({i for i, _ in ent})
+    cols = sorted({j for _, j in ent})
+    ri = {r: t for t, r in enumerate(rows)}
+    ci = {c: t for t, c in enumerate(cols)}
+    Asub, Bsub = A[rows, :], B[:, cols]
+    errs = {}
+    for s in (4, 6, 8, 10, 12):
+        C = oz.ozaki_dgemm(Asub, Bsub, "fp8", s)
+        errs[s] = exact.sampled_errors(A, B, ent, [C[ri[i], ci[j]] for i, j in ent])[0]
+    bound = 4 * k * 2.0 ** -53
+    assert errs[12] <= bound and errs[10] <= bound
+    assert errs[4] > bound                                      # too few slices must show
+    for s in (4, 6, 8):
+        ratio = errs[s + 2] / errs[s]
+        assert 2.0 ** -14 < ratio < 2.0 ** -6, (s, ratio)       # about 2^-(b+1) = 2^-5 per added slice
+    native = exact.sampled_errors(A, B, ent, [(A @ B)[i, j] for i, j in ent])[0]
+    assert errs[12] <= 4 * native + 2.0 ** -53
+
+
+def test_k_blocking_stays_at_fp64_gemm_accuracy():
+    m, n, k = 8, 8, 2048
+    A, B = inputs.phi_pair(m, n, k, 1.0, seed=3)
+    ent = [(i, j) for i in range(m) for j in range(0, n, 3)]
+    for fmt, kb, s in (("fp16", 256, 8), ("fp8", 512, 13), ("fp16", 1000, 9)):
+        C = oz.ozaki_dgemm(A, B, fmt, s, kb)
+        e_ab = exact.sampled_errors(A, B, ent, [C[i, j] for i, j in ent])[0]
+        assert e_ab <= 4 * k * 2.0 ** -53
+
+
+# ------------------------------------------------------------------ Section 4.2: integer-emulated FP64 add
+def _random_normal_doubles(rng, n, emin=-300, emax=300):
+    frac = rng.integers(0, 1 << 52, n, dtype=np.uint64)
+    e = rng.integers(emin + 1023, emax + 1023, n, dtype=np.uint64)
+    sign = rng.integers(0, 2, n, dtype=np.uint64)
+    return ((sign << np.uint64(63)) | (e << np.uint64(52)) | frac).view(np.float64)
+
+
+def test_soft_add_is_bitwise_the_host_fpu():
+    rng = np.random.default_rng(2024)
+    n = 2_000_000
+    a = _random_normal_doubles(rng, 5 * n)
+    parts = []
+    # (1) unrelated operands, (2) exponent difference within +-70, (3) near-cancellation,
+    # (4) exact ties: b = +-(odd multiple of) half an ulp of a, (5) equal exponents
+    parts.append(_random_normal_doubles(rng, n))
+    d = rng.integers(-70, 71, n)
+    parts.append(np.ldexp(_random_normal_doubles(rng, n, -1, 1), np.frexp(a[n:2 * n])[1] + d))
+    parts.append(-a[2 * n:3 * n] * (1.0 + np.ldexp(rng.integers(-8, 9, n).astype(np.float64), -rng.integers(30, 53, n))))
+    ulp = np.ldexp(1.0, np.frexp(a[3 * n:4 * n])[1] - 53)
+    parts.append(ulp * rng.choice([0.5, -0.5, 1.5, -1.5, 0.25, -0.25, 0.75], n))
+    parts.append(np.copysign(np.ldexp(_random_normal_doubles(rng, n, -1, 1), np.frexp(a[4 * n:])[1]),
+                             rng.choice([-1.0, 1.0], n)))
+    b = np.concatenate(parts)
+    assert a.size == b.size == 10_000_000
+    got = softfloat.soft_add(a, b)
+    want = a + b
+    assert np.array_equal(got.view(np.uint64), want.view(np.uint64))
+    # zeros
+    z = np.array([0.0, -0.0, 0.0, -0.0, 1.5, 0.0, -2.5])
+    w = np.array([0.0, 0.0, -0.0, -0.0, 0.0, -3.0, 2.5])
+    assert np.array_equal(softfloat.soft_add(z, w).view(np.uint64), (z + w).view(np.uint64))
+
+
+def test_emulated_accumulation_gives_the_same_bits():
+    A, B = inputs.phi_pair(24, 20, 96, 2.0, seed=4)
+    for fmt, kb in (("fp8", 0), ("fp16", 32)):
+        C_hw = oz.ozaki_dgemm(A, B, fmt, 9, kb)
+        C_sw = oz.ozaki_dgemm(A, B, fmt, 9, kb, add=softfloat.soft_add)
+        assert np.array_equal(C_hw.view(np.uint64), C_sw.view(np.uint64))
+
+
+def test_exact_reference_is_exact():
+    # closed form: sum_{i<=N} i*(N+1-i) = N(N+1)(N+2)/6, with a huge cancelling pair on top
+    N = 500
+    x = np.arange(1, N + 1, dtype=np.float64)
+    y = x[::-1].copy()
+    assert exact.exact_dot(x, y) == Fraction(N * (N + 1) * (N + 2), 6)
+    x2 = np.concatenate([x, [2.0 ** 600, -(2.0 ** 600)]])
+    y2 = np.concatenate([y, [2.0 ** 300, 2.0 ** 300]])
+    assert exact.exact_dot(x2, y2) == Fraction(N * (N + 1) * (N + 2), 6)
+    assert exact.exact_dot(np.array([0.1]), np.array([0.1])) == Fraction(0.1) * Fraction(0.1)
+    assert exact.exact_dot(np.array([-0.1, 3.0]), np.array([0.1, 1.0]), absolute=True) == Fraction(0.1) * Fraction(0.1) + 3
