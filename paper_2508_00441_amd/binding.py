@@ -1,0 +1,148 @@
+"""ctypes binding of libozaki.so: the same entry points as include/ozaki_dgemm.h, argument marshalling only.
+
+Every step of the Ozaki-scheme DGEMM runs in the HIP library; nothing here computes.  There is no CPU
+fallback: loading fails loudly if the library has not been built (python -m paper_2508_00441_amd.build).
+
+Device pointers may be given as torch CUDA tensors (their data_ptr() is passed) or as integers.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libozaki.so")
+
+SLICE_FP8_E4M3 = 0
+SLICE_FP16 = 1
+ACCUM_FP64_HW = 0
+ACCUM_FP64_INT_EMU = 1
+STATUS_OK, STATUS_INFEASIBLE, STATUS_WORKSPACE, STATUS_HIP_ERROR, STATUS_NONFINITE = 0, 1, 3, 4, 5
+MAX_SLICES = 32
+MAX_K_BLOCK = 32768
+
+SLICE_FORMATS = {"fp8": SLICE_FP8_E4M3, "fp16": SLICE_FP16}
+ACCUM_MODES = {"hw": ACCUM_FP64_HW, "emu": ACCUM_FP64_INT_EMU}
+
+#: every symbol include/ozaki_dgemm.h declares: name -> (restype, argtypes)
+_i64, _int, _vp, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+SIGNATURES = {
+    "ozaki_plan": (_int, [_i64, _int, ctypes.POINTER(_int), ctypes.POINTER(_int)]),
+    "ozaki_dgemm": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int, _int, _i64, _int]),
+    "ozaki_set_stream": (_int, [_vp]),
+    "ozaki_workspace_bytes": (_sz, [_i64, _i64, _i64, _int, _int, _i64]),
+    "ozaki_workspace_min_bytes": (_sz, [_i64, _i64, _i64, _int, _int, _i64]),
+    "ozaki_set_workspace": (_int, [_vp, _sz]),
+    "ozaki_last_device_status": (_int, []),
+    "ozaki_last_hip_error": (_int, []),
+    "ozaki_status_string": (ctypes.c_char_p, [_int]),
+    "ozaki_profile_enable": (_int, [_int]),
+    "ozaki_profile_read": (_int, [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(_int)]),
+    "ozaki_split": (_int, [_int, _i64, _i64, _vp, _i64, _int, _int, _i64, _vp, _vp]),
+    "ozaki_pair_products": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _int, _int, _i64, _vp]),
+    "ozaki_fp64_add_emulated": (_int, [_vp, _vp, _vp, _i64]),
+}
+
+_lib = None
+
+
+class OzakiError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({status_string(status)})")
+
+
+def load() -> ctypes.CDLL:
+    """Loads libozaki.so once; raises if it is missing (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} not found: build it with `python -m paper_2508_00441_amd.build`")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _ptr(x) -> int:
+    if x is None:
+        return 0
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _check(status: int, where: str) -> int:
+    if status != 0:
+        raise OzakiError(status, where)
+    return status
+
+
+def status_string(status: int) -> str:
+    return load().ozaki_status_string(status).decode()
+
+
+def ozaki_plan(k_block: int, slice_format: int) -> Tuple[int, int]:
+    """(rho, b) of Eq. 1-3 for one block length; host only."""
+    rho, b = ctypes.c_int(0), ctypes.c_int(0)
+    _check(load().ozaki_plan(k_block, slice_format, ctypes.byref(rho), ctypes.byref(b)), "ozaki_plan")
+    return rho.value, b.value
+
+
+def ozaki_set_stream(stream_handle: int) -> None:
+    _check(load().ozaki_set_stream(stream_handle), "ozaki_set_stream")
+
+
+def ozaki_workspace_bytes(m, n, k, slice_format, num_slices, k_block) -> int:
+    return int(load().ozaki_workspace_bytes(m, n, k, slice_format, num_slices, k_block))
+
+
+def ozaki_workspace_min_bytes(m, n, k, slice_format, num_slices, k_block) -> int:
+    return int(load().ozaki_workspace_min_bytes(m, n, k, slice_format, num_slices, k_block))
+
+
+def ozaki_set_workspace(buf, nbytes: int) -> None:
+    _check(load().ozaki_set_workspace(_ptr(buf), nbytes), "ozaki_set_workspace")
+
+
+def ozaki_last_device_status() -> int:
+    return int(load().ozaki_last_device_status())
+
+
+def ozaki_last_hip_error() -> int:
+    return int(load().ozaki_last_hip_error())
+
+
+def ozaki_profile_enable(on: bool) -> None:
+    _check(load().ozaki_profile_enable(1 if on else 0), "ozaki_profile_enable")
+
+
+def ozaki_profile_read():
+    """([ms_split, ms_gemm, ms_accumulate], [launches...]) accumulated since the last read."""
+    ms = (ctypes.c_float * 3)()
+    cnt = (ctypes.c_int * 3)()
+    _check(load().ozaki_profile_read(ms, cnt), "ozaki_profile_read")
+    return list(ms), list(cnt)
+
+
+def ozaki_dgemm(m, n, k, A, lda, B, ldb, C, ldc, slice_format, num_slices, k_block, accum_mode, check: bool = True) -> int:
+    st = load().ozaki_dgemm(m, n, k, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, slice_format, num_slices, k_block, accum_mode)
+    return _check(st, "ozaki_dgemm") if check else st
+
+
+def ozaki_split(is_B, rows, k, X, ldx, slice_format, num_slices, k_block, slices_out, exps_out, check: bool = True) -> int:
+    st = load().ozaki_split(is_B, rows, k, _ptr(X), ldx, slice_format, num_slices, k_block, _ptr(slices_out), _ptr(exps_out))
+    return _check(st, "ozaki_split") if check else st
+
+
+def ozaki_pair_products(m, n, k, A, lda, B, ldb, slice_format, num_slices, k_block, P_out, check: bool = True) -> int:
+    st = load().ozaki_pair_products(m, n, k, _ptr(A), lda, _ptr(B), ldb, slice_format, num_slices, k_block, _ptr(P_out))
+    return _check(st, "ozaki_pair_products") if check else st
+
+
+def ozaki_fp64_add_emulated(a, b, out, n) -> None:
+    _check(load().ozaki_fp64_add_emulated(_ptr(a), _ptr(b), _ptr(out), n), "ozaki_fp64_add_emulated")

@@ -1,0 +1,202 @@
+// Accumulation of the slice-pair products into FP64 and the final rescale (paper Section 3, Eq. 10 and the
+// paragraph after Eq. 11; Section 4.2 for the integer-emulated variant; Section 4.3 for the block sum).
+//
+// For one k-block, element (i, j):
+//     S   = sum over the pairs (p, q), least significant anti-diagonal first, of
+//           P_pq(i,j) * 2^((cA_p(i) - cA_1(i)) + (cB_q(j) - cB_1(j)))        each addition rounded to FP64
+//     C   = S * 2^(cA_1(i) + cB_1(j))            first block
+//     C  += S * 2^(cA_1(i) + cB_1(j))            later blocks (one more FP64 addition)
+// Scaling by a power of two commutes with rounding (inside the normal range), so summing with exponents
+// relative to the first slice and rescaling once gives the same bits as scaling every term by
+// 2^(cA_p + cB_q) as Eq. 10 writes it.  P_pq is the FP32 value left by the matrix unit; it already
+// contains the factor 2^-2b of the two slice entries.
+//
+// Two instantiations: hardware FP64 (convert, ldexp, add -- no multiply) and integer-only (fp64_emu.hpp),
+// which executes no FP64 instruction at all and returns the same bits.
+//
+// One workgroup handles one 32 x 32 MFMA tile position of a 256 x 256 tile (256 threads x 4 consecutive
+// columns of C each), reading the products in the order the GEMM kernel stored them.
+#include <type_traits>
+
+#include "fp64_emu.hpp"
+#include "layout.hpp"
+
+namespace ozaki {
+
+namespace {
+
+struct AccArgs {
+    const float* P;          // [nz][tiles_n][tiles_m][TILE_ELEMS]
+    double* S;               // [tiles_n][tiles_m][TILE_ELEMS] running block sum (may be null when unused)
+    double* C;
+    int64_t ldc;
+    const int32_t* ea;       // exponents of the block: [s][rows_pad_a]
+    const int32_t* eb;       // [s][rows_pad_b]
+    int64_t rows_pad_a, rows_pad_b;
+    int64_t m, n;
+    int tiles_m, tiles_n;
+    int z0, nz, s;
+    int read_S, write_S, add_to_C;
+    PairList pairs;
+};
+
+template <bool EMU>
+__global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
+    __shared__ int relA[MAX_SLICES][32];
+    __shared__ int relB[MAX_SLICES][32];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, g4 = tid >> 6;
+    const int pos = blockIdx.x & 63;                  // wave*16 + sub
+    const int tile = blockIdx.x >> 6;
+    const int tn = tile / a.tiles_m, tm = tile - tn * a.tiles_m;
+    const int wave = pos >> 4, sub = pos & 15;
+    const int wn = wave >> 1, wm = wave & 1, ti = sub >> 2, tj = sub & 3;
+    const int64_t m0 = (int64_t)tm * TILE + wm * 128 + tj * 32;       // first row of C of this 32 x 32 position
+    const int64_t n0 = (int64_t)tn * TILE + wn * 128 + ti * 32;       // first column
+
+    // exponents of the 32 rows and 32 columns: slot 0 keeps the first-slice exponent, slots p >= 1 the difference to it
+    for (int idx = tid; idx < a.s * 32; idx += 256) {
+        const int p = idx >> 5, r = idx & 31;
+        const int ca = a.ea[(int64_t)p * a.rows_pad_a + m0 + r], ca1 = a.ea[m0 + r];
+        const int cb = a.eb[(int64_t)p * a.rows_pad_b + n0 + r], cb1 = a.eb[n0 + r];
+        relA[p][r] = p == 0 ? ca1 : ca - ca1;
+        relB[p][r] = p == 0 ? cb1 : cb - cb1;
+    }
+    __syncthreads();
+
+    const int ml = lane & 31;
+    const int nl = g4 * 8 + (lane >> 5) * 4;
+    const size_t tile_off = (size_t)tile * TILE_ELEMS + (size_t)pos * 1024 + (size_t)tid * 4;
+    const size_t pair_stride = (size_t)a.tiles_m * a.tiles_n * TILE_ELEMS;
+
+    typedef typename std::conditional<EMU, uint64_t, double>::type acc_t;
+    acc_t S[4];
+    if (a.read_S) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) S[r] = reinterpret_cast<const acc_t*>(a.S)[tile_off + r];
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) S[r] = 0;
+    }
+
+    for (int z = 0; z < a.nz; ++z) {
+        const int p = a.pairs.p[a.z0 + z] - 1, q = a.pairs.q[a.z0 + z] - 1;
+        const uint4 v = *reinterpret_cast<const uint4*>(a.P + (size_t)z * pair_stride + tile_off);
+        const int eA = p == 0 ? 0 : relA[p][ml];
+        const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int e = eA + (q == 0 ? 0 : relB[q][nl + r]);
+            if constexpr (EMU) {
+                S[r] = (acc_t)fp64_add_emulated((uint64_t)S[r], fp32_bits_scaled_to_fp64(vv[r], e));
+            } else {
+                S[r] = (acc_t)((double)S[r] + ldexp((double)__uint_as_float(vv[r]), e));
+            }
+        }
+    }
+
+    if (a.write_S) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) reinterpret_cast<acc_t*>(a.S)[tile_off + r] = S[r];
+        return;
+    }
+    const int64_t mi = m0 + ml;
+    if (mi >= a.m) return;
+    const int baseA = relA[0][ml];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t nj = n0 + nl + r;
+        if (nj >= a.n) continue;
+        const int base = baseA + relB[0][nl + r];
+        acc_t* dst = reinterpret_cast<acc_t*>(a.C) + mi + nj * a.ldc;
+        if constexpr (EMU) {
+            uint64_t v = fp64_scale_pow2_emulated((uint64_t)S[r], base);
+            if (a.add_to_C) v = fp64_add_emulated((uint64_t)*dst, v);
+            *dst = (acc_t)v;
+        } else {
+            double v = ldexp((double)S[r], base);
+            if (a.add_to_C) v = (double)*dst + v;
+            *dst = (acc_t)v;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256) export_products_kernel(const float* __restrict__ P, float* __restrict__ out, int64_t m,
+                                                              int64_t n, int tiles_m, int tiles_n) {
+    // one thread per stored float; grid.y = pair
+    const size_t pair_stride = (size_t)tiles_m * tiles_n * TILE_ELEMS;
+    const int64_t z = blockIdx.y;
+    for (size_t g = (size_t)blockIdx.x * 256 + threadIdx.x; g < pair_stride; g += (size_t)gridDim.x * 256) {
+        const int tile = (int)(g / TILE_ELEMS), idx = (int)(g % TILE_ELEMS);
+        const int tn = tile / tiles_m, tm = tile - tn * tiles_m;
+        int ml, nl;
+        acc_order_to_mn(idx, ml, nl);
+        const int64_t mi = (int64_t)tm * TILE + ml, nj = (int64_t)tn * TILE + nl;
+        if (mi < m && nj < n) out[((size_t)z * n + nj) * m + mi] = P[(size_t)z * pair_stride + g];
+    }
+}
+
+__global__ void __launch_bounds__(256) add_emulated_kernel(const uint64_t* a, const uint64_t* b, uint64_t* out, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+        out[i] = fp64_add_emulated(a[i], b[i]);
+}
+
+__global__ void __launch_bounds__(256) fill_zero_kernel(uint64_t* C, int64_t ldc, int64_t m, int64_t n) {
+    const int64_t total = m * n;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256)
+        C[(i % m) + (i / m) * ldc] = 0;
+}
+
+unsigned grid_for(int64_t work_items) {
+    int64_t blocks = (work_items + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 65536) blocks = 65536;
+    return (unsigned)blocks;
+}
+
+}  // namespace
+
+hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B, const PairList& pairs,
+                             int64_t t, int z0, int nz, const float* P, double* S_io,
+                             double* C, int64_t ldc, int accum_mode, hipStream_t st) {
+    if (pl.tiles_m == 0 || pl.tiles_n == 0) return hipSuccess;
+    AccArgs a;
+    a.P = P; a.S = S_io; a.C = C; a.ldc = ldc;
+    a.ea = A.exps + (size_t)t * pl.s * A.rows_pad;
+    a.eb = B.exps + (size_t)t * pl.s * B.rows_pad;
+    a.rows_pad_a = A.rows_pad; a.rows_pad_b = B.rows_pad;
+    a.m = pl.m; a.n = pl.n; a.tiles_m = (int)pl.tiles_m; a.tiles_n = (int)pl.tiles_n;
+    a.z0 = z0; a.nz = nz; a.s = pl.s;
+    a.read_S = z0 > 0;
+    a.write_S = (z0 + nz) < pl.npairs;
+    a.add_to_C = t > 0;
+    a.pairs = pairs;
+    const int64_t blocks = pl.tiles_m * pl.tiles_n * 64;
+    if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    if (accum_mode == 1) hipLaunchKernelGGL((accumulate_kernel<true>), dim3((unsigned)blocks), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((accumulate_kernel<false>), dim3((unsigned)blocks), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_export_products(const Plan& pl, int nz, const float* P, float* out, hipStream_t st) {
+    if (nz <= 0 || pl.m == 0 || pl.n == 0) return hipSuccess;
+    dim3 grid(grid_for(pl.tiles_m * pl.tiles_n * (int64_t)TILE_ELEMS), (unsigned)nz);
+    hipLaunchKernelGGL(export_products_kernel, grid, dim3(256), 0, st, P, out, pl.m, pl.n, (int)pl.tiles_m, (int)pl.tiles_n);
+    return hipGetLastError();
+}
+
+hipError_t launch_add_emulated(const double* a, const double* b, double* out, int64_t n, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(add_emulated_kernel, dim3(grid_for(n)), dim3(256), 0, st, reinterpret_cast<const uint64_t*>(a),
+                       reinterpret_cast<const uint64_t*>(b), reinterpret_cast<uint64_t*>(out), n);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_zero_f64(double* C, int64_t ldc, int64_t m, int64_t n, hipStream_t st) {
+    if (m <= 0 || n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(grid_for(m * n)), dim3(256), 0, st, reinterpret_cast<uint64_t*>(C), ldc, m, n);
+    return hipGetLastError();
+}
+
+}  // namespace ozaki

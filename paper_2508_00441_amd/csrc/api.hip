@@ -1,0 +1,373 @@
+// C ABI of libozaki: argument checks, the planner (Eq. 1-3), workspace carve-up and the kernel sequence.
+#include <stdio.h>
+#include <string.h>
+
+#include <vector>
+
+#include "../../include/ozaki_dgemm.h"
+#include "layout.hpp"
+
+using namespace ozaki;
+
+static_assert(OZAKI_MAX_SLICES == MAX_SLICES, "header and implementation disagree");
+static_assert(OZAKI_MAX_K_BLOCK == MAX_K_BLOCK, "header and implementation disagree");
+
+namespace {
+
+struct State {
+    hipStream_t stream = nullptr;
+    uint8_t* ws = nullptr;
+    size_t ws_bytes = 0;
+    int last_hip_error = 0;
+    bool profiling = false;
+    struct Span { hipEvent_t e0, e1; int phase; };
+    std::vector<Span> spans;       // recorded since the last ozaki_profile_read
+    std::vector<hipEvent_t> pool;  // idle events
+};
+State g;
+
+constexpr size_t ALIGN = 256;
+constexpr size_t FLAG_BYTES = 256;
+constexpr size_t P_BUDGET = (size_t)32 << 30;
+size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+
+int fail_hip(hipError_t e) {
+    g.last_hip_error = (int)e;
+    return OZAKI_STATUS_HIP_ERROR;
+}
+#define HIP_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return fail_hip(e_); } while (0)
+
+// Largest b <= m2 with kb * 4^b <= 2^24 (Eq. 1-3 with Type1 = FP64, Type3 = FP32); -1 if none.
+int slice_bits(int64_t kb, int fmt) {
+    const int m2 = fmt == OZAKI_SLICE_FP16 ? 11 : 4;
+    for (int b = m2; b >= 0; --b)
+        if (kb <= ((int64_t)1 << (24 - 2 * b))) return b;
+    return -1;
+}
+
+// Builds the plan; returns 0 or a status / negative argument index in the numbering of ozaki_dgemm.
+int make_plan(int64_t m, int64_t n, int64_t k, int fmt, int s, int64_t k_block, Plan& pl) {
+    if (m < 0) return -1;
+    if (n < 0) return -2;
+    if (k < 0) return -3;
+    if (fmt != OZAKI_SLICE_FP8_E4M3 && fmt != OZAKI_SLICE_FP16) return -10;
+    if (s < 0) return -11;
+    if (k_block < 0) return -12;
+    memset(&pl, 0, sizeof(pl));
+    pl.m = m; pl.n = n; pl.k = k; pl.fmt = fmt; pl.elem_bytes = fmt == OZAKI_SLICE_FP16 ? 2 : 1;
+    pl.kb = (k_block == 0 || k_block > k) ? k : k_block;
+    if (pl.kb < 1) pl.kb = 1;
+    if (pl.kb > MAX_K_BLOCK) return OZAKI_STATUS_INFEASIBLE;
+    pl.b = slice_bits(pl.kb, fmt);
+    if (pl.b < 0) return OZAKI_STATUS_INFEASIBLE;
+    pl.rho = 53 - pl.b;
+    pl.s = s == 0 ? (61 + pl.b) / (pl.b + 1) : s;
+    if (pl.s < 1 || pl.s > MAX_SLICES) return OZAKI_STATUS_INFEASIBLE;
+    pl.T = k == 0 ? 0 : (k + pl.kb - 1) / pl.kb;
+    const int64_t epc = CHUNK_BYTES / pl.elem_bytes;
+    pl.chunks = (pl.kb + epc - 1) / epc;
+    pl.npairs = pl.s * (pl.s + 1) / 2;
+    pl.tiles_m = (m + TILE - 1) / TILE;
+    pl.tiles_n = (n + TILE - 1) / TILE;
+    pl.m_pad = pl.tiles_m * TILE;
+    pl.n_pad = pl.tiles_n * TILE;
+    return 0;
+}
+
+void make_pairs(int s, PairList& pr) {
+    int z = 0;
+    for (int gsum = s + 1; gsum >= 2; --gsum)
+        for (int p = 1; p < gsum; ++p) {
+            const int q = gsum - p;
+            if (p <= s && q <= s) { pr.p[z] = (uint8_t)p; pr.q[z] = (uint8_t)q; ++z; }
+        }
+}
+
+struct Carve {
+    int* flags;
+    double* At;
+    Operand A, B;
+    double* S;
+    float* P;
+    int chunk_pairs;
+};
+
+size_t slices_bytes(const Plan& pl, int64_t rows_pad) { return align_up((size_t)pl.T * pl.s * pl.chunks * rows_pad * CHUNK_BYTES); }
+size_t exps_bytes(const Plan& pl, int64_t rows_pad) { return align_up((size_t)pl.T * pl.s * rows_pad * sizeof(int32_t)); }
+size_t fixed_bytes(const Plan& pl) {
+    return FLAG_BYTES + align_up((size_t)pl.m * pl.k * sizeof(double)) + slices_bytes(pl, pl.m_pad) + slices_bytes(pl, pl.n_pad) +
+           exps_bytes(pl, pl.m_pad) + exps_bytes(pl, pl.n_pad);
+}
+size_t pair_bytes(const Plan& pl) { return (size_t)pl.m_pad * pl.n_pad * sizeof(float); }
+size_t sum_bytes(const Plan& pl) { return (size_t)pl.m_pad * pl.n_pad * sizeof(double); }
+
+size_t recommended_bytes(const Plan& pl) {
+    const size_t all = (size_t)pl.npairs * pair_bytes(pl);
+    if (all <= P_BUDGET) return fixed_bytes(pl) + all;
+    size_t fit = P_BUDGET / pair_bytes(pl);
+    if (fit < 1) fit = 1;
+    return fixed_bytes(pl) + sum_bytes(pl) + fit * pair_bytes(pl);
+}
+size_t minimum_bytes(const Plan& pl) {
+    if (pl.npairs == 1) return fixed_bytes(pl) + pair_bytes(pl);
+    return fixed_bytes(pl) + sum_bytes(pl) + pair_bytes(pl);
+}
+
+// Places every buffer in the workspace; returns false if it does not fit.
+bool carve(const Plan& pl, Carve& c) {
+    if (!g.ws) return false;
+    size_t off = 0;
+    c.flags = reinterpret_cast<int*>(g.ws);
+    off += FLAG_BYTES;
+    c.At = reinterpret_cast<double*>(g.ws + off);
+    off += align_up((size_t)pl.m * pl.k * sizeof(double));
+    c.A.rows = pl.m; c.A.rows_pad = pl.m_pad;
+    c.B.rows = pl.n; c.B.rows_pad = pl.n_pad;
+    c.A.slices = g.ws + off; off += slices_bytes(pl, pl.m_pad);
+    c.B.slices = g.ws + off; off += slices_bytes(pl, pl.n_pad);
+    c.A.exps = reinterpret_cast<int32_t*>(g.ws + off); off += exps_bytes(pl, pl.m_pad);
+    c.B.exps = reinterpret_cast<int32_t*>(g.ws + off); off += exps_bytes(pl, pl.n_pad);
+    if (off > g.ws_bytes) return false;
+    const size_t rest = g.ws_bytes - off, pb = pair_bytes(pl);
+    if (pb == 0) { c.S = nullptr; c.P = nullptr; c.chunk_pairs = pl.npairs; return true; }
+    if (rest >= (size_t)pl.npairs * pb) {
+        c.S = nullptr;
+        c.P = reinterpret_cast<float*>(g.ws + off);
+        c.chunk_pairs = pl.npairs;
+        return true;
+    }
+    if (rest < sum_bytes(pl) + pb) return false;
+    c.S = reinterpret_cast<double*>(g.ws + off);
+    off += sum_bytes(pl);
+    c.P = reinterpret_cast<float*>(g.ws + off);
+    size_t fit = (g.ws_bytes - off) / pb;
+    c.chunk_pairs = fit > (size_t)pl.npairs ? pl.npairs : (int)fit;
+    return c.chunk_pairs >= 1;
+}
+
+// ---- profiling spans -------------------------------------------------------------------------------------------
+hipEvent_t take_event() {
+    hipEvent_t e = nullptr;
+    if (!g.pool.empty()) { e = g.pool.back(); g.pool.pop_back(); return e; }
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+struct Phase {
+    int phase; hipEvent_t e0 = nullptr, e1 = nullptr;
+    explicit Phase(int ph) : phase(ph) {
+        if (!g.profiling) return;
+        e0 = take_event(); e1 = take_event();
+        if (e0) (void)hipEventRecord(e0, g.stream);
+    }
+    ~Phase() {
+        if (!g.profiling || !e0 || !e1) return;
+        (void)hipEventRecord(e1, g.stream);
+        g.spans.push_back({e0, e1, phase});
+    }
+};
+
+// split both operands of the plan into the carved buffers
+int run_split(const Plan& pl, const Carve& c, const double* A, int64_t lda, const double* B, int64_t ldb, bool do_a, bool do_b) {
+    Phase ph(0);
+    if (do_a && pl.m > 0) {
+        HIP_TRY(launch_transpose(A, lda, pl.m, pl.k, c.At, g.stream));
+        HIP_TRY(launch_split(c.At, pl.k, pl, c.A, c.flags, g.stream));
+    }
+    if (do_b && pl.n > 0) HIP_TRY(launch_split(B, ldb, pl, c.B, c.flags, g.stream));
+    return 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ozaki_plan(int64_t k_block, int slice_format, int* rho_out, int* bits_out) {
+    if (k_block < 1) return -1;
+    if (slice_format != OZAKI_SLICE_FP8_E4M3 && slice_format != OZAKI_SLICE_FP16) return -2;
+    const int b = slice_bits(k_block, slice_format);
+    if (b < 0) return OZAKI_STATUS_INFEASIBLE;
+    if (rho_out) *rho_out = 53 - b;
+    if (bits_out) *bits_out = b;
+    return 0;
+}
+
+int ozaki_set_stream(void* hip_stream) {
+    g.stream = reinterpret_cast<hipStream_t>(hip_stream);
+    return 0;
+}
+
+size_t ozaki_workspace_bytes(int64_t m, int64_t n, int64_t k, int slice_format, int num_slices, int64_t k_block) {
+    Plan pl;
+    if (make_plan(m, n, k, slice_format, num_slices, k_block, pl) != 0) return 0;
+    return recommended_bytes(pl);
+}
+
+size_t ozaki_workspace_min_bytes(int64_t m, int64_t n, int64_t k, int slice_format, int num_slices, int64_t k_block) {
+    Plan pl;
+    if (make_plan(m, n, k, slice_format, num_slices, k_block, pl) != 0) return 0;
+    return minimum_bytes(pl);
+}
+
+int ozaki_set_workspace(void* dev_ptr, size_t bytes) {
+    if ((dev_ptr == nullptr) != (bytes == 0)) return -1;
+    if (reinterpret_cast<uintptr_t>(dev_ptr) % ALIGN != 0) return -1;
+    if (dev_ptr && bytes < FLAG_BYTES) return -2;
+    g.ws = reinterpret_cast<uint8_t*>(dev_ptr);
+    g.ws_bytes = bytes;
+    if (g.ws) HIP_TRY(hipMemsetAsync(g.ws, 0, FLAG_BYTES, g.stream));
+    return 0;
+}
+
+int ozaki_last_device_status(void) {
+    if (!g.ws) {
+        HIP_TRY(hipStreamSynchronize(g.stream));
+        return 0;
+    }
+    int flags = 0;
+    HIP_TRY(hipMemcpyAsync(&flags, g.ws, sizeof(int), hipMemcpyDeviceToHost, g.stream));
+    HIP_TRY(hipStreamSynchronize(g.stream));
+    if (flags) HIP_TRY(hipMemsetAsync(g.ws, 0, FLAG_BYTES, g.stream));
+    return (flags & 1) ? OZAKI_STATUS_NONFINITE : 0;
+}
+
+int ozaki_last_hip_error(void) { return g.last_hip_error; }
+
+const char* ozaki_status_string(int status) {
+    switch (status) {
+        case OZAKI_STATUS_OK: return "success";
+        case OZAKI_STATUS_INFEASIBLE: return "infeasible: no exact slice width for this block length, or num_slices / k_block out of range";
+        case OZAKI_STATUS_WORKSPACE: return "workspace missing or too small";
+        case OZAKI_STATUS_HIP_ERROR: return "HIP runtime error";
+        case OZAKI_STATUS_NONFINITE: return "non-finite input";
+        default: return status < 0 ? "invalid argument (the negated value is its 1-based position)" : "unknown status";
+    }
+}
+
+int ozaki_profile_enable(int on) {
+    g.profiling = on != 0;
+    return 0;
+}
+
+int ozaki_profile_read(float* ms_out, int* launches_out) {
+    if (!ms_out) return -1;
+    HIP_TRY(hipStreamSynchronize(g.stream));
+    for (int i = 0; i < 3; ++i) { ms_out[i] = 0.0f; if (launches_out) launches_out[i] = 0; }
+    for (auto& sp : g.spans) {
+        float ms = 0.0f;
+        HIP_TRY(hipEventElapsedTime(&ms, sp.e0, sp.e1));
+        ms_out[sp.phase] += ms;
+        if (launches_out) launches_out[sp.phase] += 1;
+        g.pool.push_back(sp.e0);
+        g.pool.push_back(sp.e1);
+    }
+    g.spans.clear();
+    return 0;
+}
+
+int ozaki_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb,
+                double* C, int64_t ldc, int slice_format, int num_slices, int64_t k_block, int accum_mode) {
+    Plan pl;
+    const int st = make_plan(m, n, k, slice_format, num_slices, k_block, pl);
+    if (st != 0) return st;
+    if (accum_mode != OZAKI_ACCUM_FP64_HW && accum_mode != OZAKI_ACCUM_FP64_INT_EMU) return -13;
+    if (m == 0 || n == 0) return 0;
+    if (!C) return -8;
+    if (ldc < (m > 1 ? m : 1)) return -9;
+    if (k == 0) {
+        HIP_TRY(launch_fill_zero_f64(C, ldc, m, n, g.stream));
+        return 0;
+    }
+    if (!A) return -4;
+    if (lda < (m > 1 ? m : 1)) return -5;
+    if (!B) return -6;
+    if (ldb < (k > 1 ? k : 1)) return -7;
+    Carve c;
+    if (!carve(pl, c)) return OZAKI_STATUS_WORKSPACE;
+    PairList pairs;
+    make_pairs(pl.s, pairs);
+
+    int rc = run_split(pl, c, A, lda, B, ldb, true, true);
+    if (rc) return rc;
+    for (int64_t t = 0; t < pl.T; ++t) {
+        for (int z0 = 0; z0 < pl.npairs; z0 += c.chunk_pairs) {
+            const int nz = (pl.npairs - z0 < c.chunk_pairs) ? pl.npairs - z0 : c.chunk_pairs;
+            {
+                Phase ph(1);
+                HIP_TRY(launch_pair_gemm(pl, c.A, c.B, pairs, t, z0, nz, c.P, g.stream));
+            }
+            {
+                Phase ph(2);
+                HIP_TRY(launch_accumulate(pl, c.A, c.B, pairs, t, z0, nz, c.P, c.S, C, ldc, accum_mode, g.stream));
+            }
+        }
+    }
+    return 0;
+}
+
+int ozaki_split(int is_B, int64_t rows, int64_t k, const double* X, int64_t ldx, int slice_format, int num_slices,
+                int64_t k_block, void* slices_out, int32_t* exps_out) {
+    if (is_B != 0 && is_B != 1) return -1;
+    if (rows < 0) return -2;
+    if (k < 0) return -3;
+    if (num_slices < 1) return -7;
+    Plan pl;
+    // plan with the operand in the role it has in the product; the other dimension is irrelevant here
+    const int st = make_plan(is_B ? 0 : rows, is_B ? rows : 0, k, slice_format, num_slices, k_block, pl);
+    if (st < 0) return st == -10 ? -6 : st == -12 ? -8 : st;
+    if (st != 0) return st;
+    if (rows == 0 || k == 0) return 0;
+    if (!X) return -4;
+    if (ldx < (is_B ? (k > 1 ? k : 1) : (rows > 1 ? rows : 1))) return -5;
+    if (!slices_out) return -9;
+    if (!exps_out) return -10;
+    Carve c;
+    if (!carve(pl, c)) return OZAKI_STATUS_WORKSPACE;
+    int rc = run_split(pl, c, X, ldx, X, ldx, !is_B, is_B != 0);
+    if (rc) return rc;
+    const Operand& op = is_B ? c.B : c.A;
+    HIP_TRY(launch_export_slices(pl, op, slices_out, g.stream));
+    // exponents: [T][s][rows_pad] -> [T][s][rows]
+    HIP_TRY(hipMemcpy2DAsync(exps_out, (size_t)rows * sizeof(int32_t), op.exps, (size_t)op.rows_pad * sizeof(int32_t),
+                             (size_t)rows * sizeof(int32_t), (size_t)pl.T * pl.s, hipMemcpyDeviceToDevice, g.stream));
+    return 0;
+}
+
+int ozaki_pair_products(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb,
+                        int slice_format, int num_slices, int64_t k_block, float* P_out) {
+    Plan pl;
+    int st = make_plan(m, n, k, slice_format, num_slices, k_block, pl);
+    if (st < 0) return st == -10 ? -8 : st == -11 ? -9 : st == -12 ? -10 : st;
+    if (st != 0) return st;
+    if (num_slices < 1) return -9;
+    if (m == 0 || n == 0 || k == 0) return 0;
+    if (!A) return -4;
+    if (lda < m) return -5;
+    if (!B) return -6;
+    if (ldb < k) return -7;
+    if (!P_out) return -11;
+    Carve c;
+    if (!carve(pl, c)) return OZAKI_STATUS_WORKSPACE;
+    PairList pairs;
+    make_pairs(pl.s, pairs);
+    int rc = run_split(pl, c, A, lda, B, ldb, true, true);
+    if (rc) return rc;
+    for (int64_t t = 0; t < pl.T; ++t)
+        for (int z0 = 0; z0 < pl.npairs; z0 += c.chunk_pairs) {
+            const int nz = (pl.npairs - z0 < c.chunk_pairs) ? pl.npairs - z0 : c.chunk_pairs;
+            HIP_TRY(launch_pair_gemm(pl, c.A, c.B, pairs, t, z0, nz, c.P, g.stream));
+            HIP_TRY(launch_export_products(pl, nz, c.P, P_out + ((size_t)t * pl.npairs + z0) * (size_t)m * n, g.stream));
+        }
+    return 0;
+}
+
+int ozaki_fp64_add_emulated(const double* a, const double* b, double* out, int64_t n) {
+    if (n < 0) return -4;
+    if (n == 0) return 0;
+    if (!a) return -1;
+    if (!b) return -2;
+    if (!out) return -3;
+    HIP_TRY(launch_add_emulated(a, b, out, n, g.stream));
+    return 0;
+}
+
+}  // extern "C"

@@ -1,0 +1,107 @@
+// IEEE binary64 addition with 32/64-bit integer instructions only (paper Section 4.2).
+//
+// Round-to-nearest-even, bitwise equal to a hardware FP64 add for operands and results that are
+// zeros or normal numbers.  As in the paper, overflow, underflow and subnormal numbers are not
+// handled: a result below the normal range is flushed to a signed zero, one above it becomes a
+// signed infinity, and subnormal operands are treated as zeros.
+//
+// The significands carry three extra low bits (guard, round, sticky); that is enough because an
+// effective subtraction either has an exponent difference <= 1 (then it is exact and may need a
+// long normalisation shift) or needs at most a one-bit normalisation shift.
+//
+// The header compiles for the device (hipcc) and, for CPU-side unit tests of this very code, for the
+// host (any C++ compiler): OZAKI_HD expands to nothing there.
+#pragma once
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#include <hip/hip_runtime.h>
+#define OZAKI_HD __host__ __device__ __forceinline__
+#else
+#define OZAKI_HD inline
+#endif
+
+namespace ozaki {
+
+OZAKI_HD int clz64(uint64_t v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __clzll((long long)v);
+#else
+    return __builtin_clzll(v);
+#endif
+}
+
+constexpr uint64_t F64_SIGN = 0x8000000000000000ull;
+constexpr uint64_t F64_FRAC = 0x000FFFFFFFFFFFFFull;
+constexpr uint64_t F64_HIDDEN = 0x0010000000000000ull;
+constexpr uint64_t F64_INF = 0x7FF0000000000000ull;
+
+// a (+) b on raw bit patterns.
+OZAKI_HD uint64_t fp64_add_emulated(uint64_t a, uint64_t b) {
+    uint64_t abs_a = a & ~F64_SIGN, abs_b = b & ~F64_SIGN;
+    // Zeros (and subnormals, by contract): x + 0 = x; (+0) + (-0) = +0.
+    if (abs_b < F64_HIDDEN) return (abs_a < F64_HIDDEN) ? (a & b & F64_SIGN) : a;
+    if (abs_a < F64_HIDDEN) return b;
+    if (abs_a < abs_b) {                       // order by magnitude
+        uint64_t t = a; a = b; b = t;
+        t = abs_a; abs_a = abs_b; abs_b = t;
+    }
+    int e = (int)(abs_a >> 52);
+    int d = e - (int)(abs_b >> 52);
+    uint64_t ma = ((abs_a & F64_FRAC) | F64_HIDDEN) << 3;    // hidden bit at position 55
+    uint64_t mb = ((abs_b & F64_FRAC) | F64_HIDDEN) << 3;
+    if (d > 0) {
+        if (d >= 57) {
+            mb = 1;                                            // pure sticky
+        } else {
+            uint64_t lost = mb & ((1ull << d) - 1);
+            mb = (mb >> d) | (lost != 0);
+        }
+    }
+    uint64_t sign = a & F64_SIGN;
+    uint64_t m;
+    if ((a ^ b) & F64_SIGN) {
+        m = ma - mb;
+        if (m == 0) return 0;                                  // exact cancellation gives +0
+        int lz = clz64(m) - 8;                                 // bring the leading bit back to position 55
+        m <<= lz;
+        e -= lz;
+    } else {
+        m = ma + mb;
+        if (m >> 56) {                                         // carry out: one step right, keep the sticky bit
+            m = (m >> 1) | (m & 1);
+            e += 1;
+        }
+    }
+    uint64_t sig = m >> 3;                                     // 53 bits, hidden bit at position 52
+    unsigned grs = (unsigned)m & 7u;
+    sig += (grs > 4u) | ((grs == 4u) & (unsigned)(sig & 1));   // ties to even; a carry to 2^53 is absorbed below
+    if (e <= 0) return sign;
+    uint64_t r = ((uint64_t)e << 52) + (sig - F64_HIDDEN);     // sig == 2^53 bumps the exponent, fraction 0
+    if (r >= F64_INF) return sign | F64_INF;
+    return sign | r;
+}
+
+// Exact conversion of a normal (or zero) FP32 bit pattern times 2^e2 to FP64 bits, integer-only.
+// Returns 0 for a zero input.  The caller guarantees the result stays in the normal FP64 range,
+// except that a too small result is flushed to zero.
+OZAKI_HD uint64_t fp32_bits_scaled_to_fp64(uint32_t f, int e2) {
+    if ((f << 1) == 0) return 0;
+    uint64_t sign = (uint64_t)(f >> 31) << 63;
+    int e = (int)((f >> 23) & 0xFF) - 127 + 1023 + e2;
+    if (e <= 0) return 0;
+    if (e >= 2047) return sign | F64_INF;
+    return sign | ((uint64_t)e << 52) | ((uint64_t)(f & 0x7FFFFFu) << 29);
+}
+
+// x * 2^e2 on FP64 bits (zeros stay zeros; the result is flushed / saturated outside the normal range).
+OZAKI_HD uint64_t fp64_scale_pow2_emulated(uint64_t x, int e2) {
+    uint64_t ax = x & ~F64_SIGN;
+    if (ax < F64_HIDDEN) return x & F64_SIGN;
+    int e = (int)(ax >> 52) + e2;
+    if (e <= 0) return x & F64_SIGN;
+    if (e >= 2047) return (x & F64_SIGN) | F64_INF;
+    return (x & (F64_SIGN | F64_FRAC)) | ((uint64_t)e << 52);
+}
+
+}  // namespace ozaki

@@ -1,0 +1,92 @@
+// Plan, internal data layouts and kernel-launcher prototypes shared by the libozaki translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ozaki {
+
+constexpr int MAX_SLICES = 32;
+constexpr int MAX_PAIRS = MAX_SLICES * (MAX_SLICES + 1) / 2;
+constexpr int64_t MAX_K_BLOCK = 32768;
+
+// ---- tiling of the slice-pair GEMM: one workgroup computes one TILE x TILE block of one pair product ------
+constexpr int TILE = 256;
+constexpr int CHUNK_BYTES = 128;          // bytes of the inner dimension per row staged per pipeline step
+constexpr int TILE_ELEMS = TILE * TILE;
+
+// ---- slice storage ---------------------------------------------------------------------------------------
+// One slice matrix (block t, slice p) of an operand is stored as [chunk kc][vector r][CHUNK_BYTES]:
+// the 256 vectors a workgroup stages for one pipeline step are 32 KiB of contiguous memory.  The number
+// of vectors is padded to a multiple of TILE and every block to whole chunks; the padding holds zero
+// codes, which contribute exact zeros to every product.
+struct Operand {
+    int64_t rows;         // real vectors: m for A (its rows), n for B (its columns)
+    int64_t rows_pad;     // multiple of TILE
+    uint8_t* slices;      // [T][s][chunks][rows_pad][CHUNK_BYTES]
+    int32_t* exps;        // [T][s][rows_pad]   exponent c of Eq. 4 (0 for padding vectors)
+};
+
+struct Plan {
+    int64_t m, n, k;
+    int fmt;              // 0 = FP8 E4M3, 1 = FP16
+    int elem_bytes;
+    int s;                // slices per operand
+    int b;                // magnitude bits of a slice entry (53 - rho)
+    int rho;
+    int64_t kb;           // block length (elements)
+    int64_t T;            // number of blocks
+    int64_t chunks;       // chunks per block
+    int npairs;           // s(s+1)/2
+    int64_t tiles_m, tiles_n;
+    int64_t m_pad, n_pad;
+};
+
+// Slice pairs in accumulation order (least significant anti-diagonal first), 1-based slice indices.
+struct PairList {
+    uint8_t p[MAX_PAIRS];
+    uint8_t q[MAX_PAIRS];
+};
+
+// ---- pair-product storage ("accumulator order") ------------------------------------------------------------
+// The FP32 product of one pair is stored tile by tile, [tile_n][tile_m][TILE_ELEMS], and inside a tile in
+// the order the matrix unit leaves it in the registers of the workgroup's four waves:
+//     float index = ((((wave*16 + sub)*4 + a)*64 + lane)*4 + r
+//     wave = wn*2 + wm (wn, wm in {0,1});  sub = ti*4 + tj (ti, tj in 0..3)
+//     column of C (n) = tile_n*256 + wn*128 + ti*32 + a*8 + (lane/32)*4 + r
+//     row    of C (m) = tile_m*256 + wm*128 + tj*32 + lane%32
+// Every wave-wide store / load of this buffer is one contiguous kilobyte.
+__host__ __device__ inline void acc_order_to_mn(int idx, int& m_in_tile, int& n_in_tile) {
+    int r = idx & 3, lane = (idx >> 2) & 63, a = (idx >> 8) & 3, sub = (idx >> 10) & 15, wave = idx >> 14;
+    int ti = sub >> 2, tj = sub & 3, wn = wave >> 1, wm = wave & 1;
+    n_in_tile = wn * 128 + ti * 32 + a * 8 + (lane >> 5) * 4 + r;
+    m_in_tile = wm * 128 + tj * 32 + (lane & 31);
+}
+
+// ---- launchers (each enqueues on `st` and returns the launch status) ----------------------------------------
+hipError_t launch_transpose(const double* A, int64_t lda, int64_t m, int64_t k, double* At, hipStream_t st);
+
+// Vectors are contiguous: vector r starts at X + r*ldv and has k entries.  Writes the internal layout.
+hipError_t launch_split(const double* X, int64_t ldv, const Plan& pl, const Operand& op, int* flags, hipStream_t st);
+
+// Internal layout -> plain vector-major codes (verification export).
+hipError_t launch_export_slices(const Plan& pl, const Operand& op, void* out, hipStream_t st);
+
+// Products of pairs [z0, z0+nz) of block t into P ([nz][tiles_n][tiles_m][TILE_ELEMS] floats).
+hipError_t launch_pair_gemm(const Plan& pl, const Operand& A, const Operand& B, const PairList& pairs,
+                            int64_t t, int z0, int nz, float* P, hipStream_t st);
+
+// Accumulate pairs [z0, z0+nz) of block t.  S_io: running block sum in accumulator order (read when z0 > 0,
+// written unless the chunk is the block's last one).  On the last chunk the block sum is rescaled by the
+// first-slice exponents and stored to C (t == 0) or added to C (t > 0).
+hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B, const PairList& pairs,
+                             int64_t t, int z0, int nz, const float* P, double* S_io,
+                             double* C, int64_t ldc, int accum_mode, hipStream_t st);
+
+// P in accumulator order -> [nz][n][m] column-major matrices (verification export).
+hipError_t launch_export_products(const Plan& pl, int nz, const float* P, float* out, hipStream_t st);
+
+hipError_t launch_add_emulated(const double* a, const double* b, double* out, int64_t n, hipStream_t st);
+hipError_t launch_fill_zero_f64(double* C, int64_t ldc, int64_t m, int64_t n, hipStream_t st);
+
+}  // namespace ozaki

@@ -1,0 +1,267 @@
+// Slicing of the FP64 operands into Type2 slices (paper Section 3, Eq. 4-8), integer arithmetic only.
+//
+// For a vector x (a row of A or a column of B restricted to one k-block) and p = 1..s:
+//     c   = smallest integer with max|x^(p)| <= 2^c   (Eq. 4, evaluated exactly; 0 for a zero vector)
+//     q_i = x^(p)_i / 2^(c-b) rounded to the nearest integer, ties to even       (Eq. 5-6)
+//     x^(p+1)_i = x^(p)_i - q_i 2^(c-b)                                            (Eq. 7, exact)
+//     slice^(p)_i = q_i 2^-b stored in Type2                                       (Eq. 8)
+// Eq. 5-6 obtain q through (x + sigma) - sigma with sigma = 0.75 * 2^(rho+c) in FP64: x + sigma lies in the
+// binade whose unit in the last place is 2^(rho+c-53) = 2^(c-b), sigma is an even multiple of that unit,
+// so the FP64 addition rounds x to the nearest multiple of 2^(c-b) with ties to even q, and the
+// subtraction of sigma is exact.  The kernel computes the same q directly on the bit pattern: every
+// element is kept as a signed 64-bit integer `mant` with a fixed power-of-two unit 2^E (x = mant * 2^E),
+// which represents the input and every remainder exactly; no FP64 instruction is executed.
+//
+// A vector is held in the registers of TPR threads (8*U consecutive elements per thread in U groups of
+// eight) for all s slices, so HBM sees each input element once and each slice code once.
+#include "layout.hpp"
+
+namespace ozaki {
+
+namespace {
+
+__global__ void __launch_bounds__(256) transpose_kernel(const double* __restrict__ A, int64_t lda, int64_t m, int64_t k,
+                                                        double* __restrict__ At) {
+    __shared__ double tile[32][33];
+    const int64_t i0 = (int64_t)blockIdx.x * 32, k0 = (int64_t)blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int j = ty; j < 32; j += 8) {
+        int64_t i = i0 + tx, kk = k0 + j;
+        if (i < m && kk < k) tile[j][tx] = A[i + kk * lda];
+    }
+    __syncthreads();
+    for (int j = ty; j < 32; j += 8) {
+        int64_t i = i0 + j, kk = k0 + tx;
+        if (i < m && kk < k) At[i * k + kk] = tile[tx][j];
+    }
+}
+
+struct SplitArgs {
+    const double* X;       // vector r starts at X + r*ldv
+    int64_t ldv;
+    int64_t rows, rows_pad;
+    int64_t k, kb;
+    int64_t chunks;        // chunks per block
+    int s, b;
+    int vec_ok;            // 16-byte aligned loads allowed
+    uint8_t* slices;
+    int32_t* exps;
+    int* flags;
+};
+
+constexpr int NO_ELEM = -(1 << 30);
+
+template <bool FP16>
+__device__ __forceinline__ uint32_t encode_type2(int q, int b) {
+    // code of the value q * 2^-b, |q| <= 2^b; every such value is a normal number of the format
+    if (q == 0) return 0;
+    uint32_t a = (uint32_t)(q < 0 ? -q : q);
+    int L = 32 - __clz((int)a);                       // 2^(L-1) <= a < 2^L
+    if (FP16) {
+        uint32_t frac = ((a << 11) >> L) & 0x3FFu;    // the 10 bits below the leading one
+        return ((q < 0) ? 0x8000u : 0u) | ((uint32_t)(L - 1 - b + 15) << 10) | frac;
+    } else {
+        uint32_t frac = ((a << 4) >> L) & 0x7u;       // the 3 bits below the leading one (a <= 16)
+        return ((q < 0) ? 0x80u : 0u) | ((uint32_t)(L - 1 - b + 7) << 3) | frac;
+    }
+}
+
+template <int U, int TPR, bool FP16>
+__global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArgs a) {
+    constexpr int BLOCK = TPR < 256 ? 256 : TPR;
+    constexpr int RPB = BLOCK / TPR;                  // vectors per workgroup
+    constexpr int EPC = FP16 ? CHUNK_BYTES / 2 : CHUNK_BYTES;   // elements per chunk
+    constexpr int WAVES_PER_ROW = TPR / 64;
+    __shared__ int red[2][BLOCK / 64];
+
+    const int tr = threadIdx.x % TPR;
+    const int64_t row = (int64_t)blockIdx.x * RPB + threadIdx.x / TPR;
+    const int64_t t = blockIdx.y;
+    const int64_t k0 = t * a.kb;
+    int64_t klen = a.k - k0;
+    if (klen > a.kb) klen = a.kb;
+    if (row >= a.rows) klen = 0;                      // padding vectors are all zero
+    const int64_t padded = a.chunks * EPC;
+
+    int64_t mant[8 * U];
+    int ex[8 * U];
+    bool nonfinite = false;
+    const double* src = a.X + row * a.ldv + k0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t ke = 8 * ((int64_t)tr + (int64_t)TPR * u);
+        uint64_t bits[8];
+        if (a.vec_ok && ke + 8 <= klen) {
+            const ulonglong2* v = reinterpret_cast<const ulonglong2*>(src + ke);
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                ulonglong2 w = v[h];
+                bits[2 * h] = w.x;
+                bits[2 * h + 1] = w.y;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) bits[e] = (ke + e < klen) ? __double_as_longlong(src[ke + e]) : 0ull;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint64_t w = bits[e];
+            const int e11 = (int)((w >> 52) & 0x7FF);
+            uint64_t mm = w & 0x000FFFFFFFFFFFFFull;
+            nonfinite |= (e11 == 0x7FF);
+            int E = -1074;
+            if (e11 != 0) { mm |= 0x0010000000000000ull; E = e11 - 1075; }
+            mant[8 * u + e] = (w >> 63) ? -(int64_t)mm : (int64_t)mm;
+            ex[8 * u + e] = E;
+        }
+    }
+    if (nonfinite) atomicOr(a.flags, 1);
+
+    for (int p = 0; p < a.s; ++p) {
+        // ---- Eq. 4: c = max over the vector of (smallest c_i with |x_i| <= 2^c_i)
+        int cmax = NO_ELEM;
+#pragma unroll
+        for (int i = 0; i < 8 * U; ++i) {
+            const int64_t mv = mant[i];
+            const uint64_t av = (uint64_t)(mv < 0 ? -mv : mv);
+            const int L = 64 - __clzll((long long)av);                 // bit length (0 for av == 0)
+            const int ci = ex[i] + L - (((av & (av - 1)) == 0) ? 1 : 0);  // exact power of two: one less
+            cmax = (av != 0 && ci > cmax) ? ci : cmax;
+        }
+#pragma unroll
+        for (int off = 1; off < (TPR < 64 ? TPR : 64); off <<= 1) {
+            const int o = __shfl_xor(cmax, off, 64);
+            cmax = o > cmax ? o : cmax;
+        }
+        if (WAVES_PER_ROW > 1) {
+            const int wave = threadIdx.x >> 6;
+            if ((threadIdx.x & 63) == 0) red[p & 1][wave] = cmax;
+            __syncthreads();
+            const int w0 = (wave / WAVES_PER_ROW) * WAVES_PER_ROW;
+#pragma unroll
+            for (int w = 0; w < WAVES_PER_ROW; ++w) {
+                const int o = red[p & 1][w0 + w];
+                cmax = o > cmax ? o : cmax;
+            }
+        }
+        const int c = (cmax == NO_ELEM) ? 0 : cmax;
+        const int unit = c - a.b;                                      // the slice's unit is 2^(c-b)
+
+        // ---- Eq. 5-8 element by element, eight codes per store
+        uint8_t* const dst_slice = a.slices + (size_t)((t * a.s + p) * a.chunks) * (size_t)a.rows_pad * CHUNK_BYTES;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            uint32_t codes[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int i = 8 * u + e;
+                const int64_t mv = mant[i];
+                const int sh = unit - ex[i];
+                int q = 0;
+                if (mv != 0) {
+                    if (sh <= 0) {                                     // the element is a multiple of the unit
+                        q = (int)(mv << (-sh));
+                        mant[i] = 0;
+                    } else if (sh < 55) {
+                        const uint64_t av = (uint64_t)(mv < 0 ? -mv : mv);
+                        uint64_t qa = av >> sh;
+                        const uint64_t rem = av & ((1ull << sh) - 1);
+                        const uint64_t half = 1ull << (sh - 1);
+                        const uint64_t up = (rem > half) | ((rem == half) & (qa & 1));   // nearest, ties to even
+                        qa += up;
+                        const int64_t r = (int64_t)rem - (int64_t)(up << sh);           // signed remainder
+                        q = (mv < 0) ? -(int)qa : (int)qa;
+                        mant[i] = (mv < 0) ? -r : r;
+                    }                                                  // sh >= 55: |x| < unit/4, q = 0
+                }
+                codes[e] = encode_type2<FP16>(q, a.b);
+            }
+            const int64_t ke = 8 * ((int64_t)tr + (int64_t)TPR * u);
+            if (ke < padded) {
+                const int64_t kc = ke / EPC;
+                uint8_t* dst = dst_slice + ((size_t)kc * a.rows_pad + row) * CHUNK_BYTES + (ke % EPC) * (FP16 ? 2 : 1);
+                if (FP16) {
+                    uint4 w;
+                    w.x = codes[0] | (codes[1] << 16);
+                    w.y = codes[2] | (codes[3] << 16);
+                    w.z = codes[4] | (codes[5] << 16);
+                    w.w = codes[6] | (codes[7] << 16);
+                    *reinterpret_cast<uint4*>(dst) = w;
+                } else {
+                    uint2 w;
+                    w.x = codes[0] | (codes[1] << 8) | (codes[2] << 16) | (codes[3] << 24);
+                    w.y = codes[4] | (codes[5] << 8) | (codes[6] << 16) | (codes[7] << 24);
+                    *reinterpret_cast<uint2*>(dst) = w;
+                }
+            }
+        }
+        if (tr == 0) a.exps[(t * a.s + p) * a.rows_pad + row] = c;
+    }
+}
+
+template <bool FP16>
+__global__ void __launch_bounds__(256) export_slices_kernel(const uint8_t* __restrict__ slices, int64_t rows, int64_t rows_pad,
+                                                            int64_t k, int64_t kb, int64_t chunks, int s, void* out) {
+    // plain layout: block t starts at s*rows*(t*kb) entries; inside, [p][row][kb_t]
+    constexpr int EPC = FP16 ? CHUNK_BYTES / 2 : CHUNK_BYTES;
+    const int64_t t = blockIdx.z, p = blockIdx.y;
+    int64_t klen = k - t * kb;
+    if (klen > kb) klen = kb;
+    const int64_t total = rows * klen;
+    const uint8_t* src = slices + (size_t)((t * s + p) * chunks) * (size_t)rows_pad * CHUNK_BYTES;
+    const size_t out_base = (size_t)s * rows * (t * kb) + (size_t)p * rows * klen;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+        const int64_t r = idx / klen, kk = idx % klen;
+        const size_t off = ((size_t)(kk / EPC) * rows_pad + r) * CHUNK_BYTES + (kk % EPC) * (FP16 ? 2 : 1);
+        if (FP16) reinterpret_cast<uint16_t*>(out)[out_base + idx] = *reinterpret_cast<const uint16_t*>(src + off);
+        else reinterpret_cast<uint8_t*>(out)[out_base + idx] = src[off];
+    }
+}
+
+template <int U, int TPR>
+hipError_t launch_split_cfg(const SplitArgs& a, bool fp16, int64_t T, hipStream_t st) {
+    constexpr int BLOCK = TPR < 256 ? 256 : TPR;
+    constexpr int RPB = BLOCK / TPR;
+    dim3 grid((unsigned)((a.rows_pad + RPB - 1) / RPB), (unsigned)T);
+    if (fp16) hipLaunchKernelGGL((split_kernel<U, TPR, true>), grid, dim3(BLOCK), 0, st, a);
+    else hipLaunchKernelGGL((split_kernel<U, TPR, false>), grid, dim3(BLOCK), 0, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_transpose(const double* A, int64_t lda, int64_t m, int64_t k, double* At, hipStream_t st) {
+    if (m == 0 || k == 0) return hipSuccess;
+    dim3 grid((unsigned)((m + 31) / 32), (unsigned)((k + 31) / 32));
+    hipLaunchKernelGGL(transpose_kernel, grid, dim3(256), 0, st, A, lda, m, k, At);
+    return hipGetLastError();
+}
+
+hipError_t launch_split(const double* X, int64_t ldv, const Plan& pl, const Operand& op, int* flags, hipStream_t st) {
+    SplitArgs a;
+    a.X = X; a.ldv = ldv; a.rows = op.rows; a.rows_pad = op.rows_pad; a.k = pl.k; a.kb = pl.kb; a.chunks = pl.chunks;
+    a.s = pl.s; a.b = pl.b; a.slices = op.slices; a.exps = op.exps; a.flags = flags;
+    a.vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0) && (ldv % 2 == 0) && (pl.kb % 2 == 0 || pl.T == 1);
+    const bool fp16 = pl.fmt == 1;
+    const int64_t octets = pl.chunks * (CHUNK_BYTES / pl.elem_bytes) / 8;      // per vector and block, padded
+    if (octets <= 64) return launch_split_cfg<1, 64>(a, fp16, pl.T, st);
+    if (octets <= 128) return launch_split_cfg<2, 64>(a, fp16, pl.T, st);
+    if (octets <= 256) return launch_split_cfg<4, 64>(a, fp16, pl.T, st);
+    if (octets <= 512) return launch_split_cfg<8, 64>(a, fp16, pl.T, st);
+    if (octets <= 1024) return launch_split_cfg<4, 256>(a, fp16, pl.T, st);
+    if (octets <= 2048) return launch_split_cfg<8, 256>(a, fp16, pl.T, st);
+    if (octets <= 4096) return launch_split_cfg<4, 1024>(a, fp16, pl.T, st);
+    return hipErrorInvalidValue;                                                // the planner rejects longer blocks
+}
+
+hipError_t launch_export_slices(const Plan& pl, const Operand& op, void* out, hipStream_t st) {
+    if (op.rows == 0 || pl.k == 0) return hipSuccess;
+    dim3 grid(1024, (unsigned)pl.s, (unsigned)pl.T);
+    if (pl.fmt == 1)
+        hipLaunchKernelGGL((export_slices_kernel<true>), grid, dim3(256), 0, st, op.slices, op.rows, op.rows_pad, pl.k, pl.kb, pl.chunks, pl.s, out);
+    else
+        hipLaunchKernelGGL((export_slices_kernel<false>), grid, dim3(256), 0, st, op.slices, op.rows, op.rows_pad, pl.k, pl.kb, pl.chunks, pl.s, out);
+    return hipGetLastError();
+}
+
+}  // namespace ozaki

@@ -1,0 +1,309 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bars: slices, exponents and slice-pair products bit-exact; C bit-exact against the oracle as well,
+because the library accumulates in the oracle's order (that is stronger than the required error bound,
+which is checked too, against the exact big-integer product).
+"""
+import math
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from oracle import exact, ozaki_oracle as oz, softfloat  # noqa: E402
+from paper_2508_00441_amd import binding as lib, device, inputs  # noqa: E402
+
+FMT = lib.SLICE_FORMATS
+ACC = lib.ACCUM_MODES
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    lib.load()
+    yield
+    lib.ozaki_set_workspace(None, 0)
+
+
+def _gpu_split(X_rows_np, is_B, fmt, s, k_block):
+    """X_rows_np: (rows, k) array of the vectors.  Returns codes [T][s] arrays and exps [T][s]."""
+    rows, k = X_rows_np.shape
+    if is_B:
+        Xd = torch.from_numpy(np.ascontiguousarray(X_rows_np)).cuda()            # column-major k x rows, ldx = k
+        ldx = k
+        ws = device.Workspace.for_problem(0, rows, k, FMT[fmt], s, k_block)
+    else:
+        Xd = torch.from_numpy(np.ascontiguousarray(X_rows_np.T)).cuda()          # column-major rows x k, ldx = rows
+        ldx = rows
+        ws = device.Workspace.for_problem(rows, 0, k, FMT[fmt], s, k_block)
+    plan = oz.make_plan(k, fmt, k_block)
+    T = plan.num_blocks
+    dt = torch.uint8 if fmt == "fp8" else torch.int16
+    slices = torch.zeros(s * rows * k, dtype=dt, device="cuda")
+    exps = torch.zeros(T * s * rows, dtype=torch.int32, device="cuda")
+    lib.ozaki_split(int(is_B), rows, k, Xd, ldx, FMT[fmt], s, k_block, slices, exps)
+    assert lib.ozaki_last_device_status() == 0
+    sl = slices.cpu().numpy()
+    if fmt == "fp16":
+        sl = sl.view(np.uint16)
+    ex = exps.cpu().numpy().reshape(T, s, rows)
+    codes = []
+    off = 0
+    for t in range(T):
+        kb_t = min(plan.k_block, k - t * plan.k_block)
+        blk = sl[off: off + s * rows * kb_t].reshape(s, rows, kb_t)
+        off += s * rows * kb_t
+        codes.append(blk)
+    ws.close()
+    return codes, ex
+
+
+SPLIT_CASES = [
+    # fmt, rows, k, k_block, s, phi
+    ("fp8", 256, 256, 0, 12, 0.5),
+    ("fp8", 300, 1000, 0, 9, 4.0),        # ragged rows and k (not multiples of the tile / chunk)
+    ("fp8", 77, 1000, 384, 7, 2.0),       # three blocks, last one short
+    ("fp16", 130, 1024, 0, 8, 1.0),
+    ("fp16", 65, 2100, 1024, 6, 2.0),
+    ("fp8", 40, 8192, 0, 16, 4.0),        # one workgroup per vector
+    ("fp8", 9, 20000, 0, 5, 1.0),         # 1024-thread configuration
+    ("fp16", 33, 16384, 4096, 9, 1.0),
+    ("fp8", 17, 3, 0, 4, 1.0),            # tiny k
+]
+
+
+@pytest.mark.parametrize("fmt,rows,k,k_block,s,phi", SPLIT_CASES)
+@pytest.mark.parametrize("is_B", [0, 1])
+def test_split_is_bit_exact(fmt, rows, k, k_block, s, phi, is_B):
+    rng = np.random.default_rng(100 + rows + k)
+    X = inputs.phi_matrix(rows, k, phi, rng)
+    X[0, :] = 0.0
+    if rows > 3:
+        X[1, :] = 1.0
+        X[2, :] = np.nextafter(1.0, 2.0)
+        X[3, : k // 2] = 0.0
+    if rows > 5:
+        X[4, :] *= 2.0 ** -1040            # subnormal inputs are still sliced exactly
+        X[5, :] *= 2.0 ** 600
+    ref_codes, ref_exps, plan = oz.split_operand(X, fmt, s, k_block)
+    got_codes, got_exps = _gpu_split(X, is_B, fmt, s, k_block)
+    for t in range(plan.num_blocks):
+        for p in range(s):
+            assert np.array_equal(got_exps[t][p], ref_exps[t][p]), (t, p)
+            assert np.array_equal(got_codes[t][p], ref_codes[t][p]), (t, p)
+
+
+def _upload(A, B):
+    return device.to_device_colmajor(A), device.to_device_colmajor(B)
+
+
+PRODUCT_CASES = [
+    ("fp8", 256, 256, 256, 0, 12, 0.5),
+    ("fp8", 300, 270, 520, 0, 6, 2.0),
+    ("fp8", 100, 600, 1000, 384, 5, 4.0),
+    ("fp16", 260, 130, 1100, 512, 5, 1.0),
+    ("fp16", 64, 64, 4096, 0, 4, 1.0),
+]
+
+
+@pytest.mark.parametrize("fmt,m,n,k,k_block,s,phi", PRODUCT_CASES)
+def test_pair_products_are_bit_exact(fmt, m, n, k, k_block, s, phi):
+    A, B = inputs.phi_pair(m, n, k, phi, seed=m + n + k)
+    Ad, Bd = _upload(A, B)
+    plan = oz.make_plan(k, fmt, k_block)
+    T, npairs = plan.num_blocks, s * (s + 1) // 2
+    ws = device.Workspace.for_problem(m, n, k, FMT[fmt], s, k_block)
+    P = torch.full((T, npairs, n, m), float("nan"), dtype=torch.float32, device="cuda")
+    lib.ozaki_pair_products(m, n, k, Ad, m, Bd, k, FMT[fmt], s, k_block, P)
+    assert lib.ozaki_last_device_status() == 0
+    Pn = P.cpu().numpy()
+    _, blocks = oz.ozaki_dgemm(A, B, fmt, s, k_block, return_blocks=True)
+    for t, br in enumerate(blocks):
+        assert br.pairs == oz.pair_order(s)
+        for z, Pref in enumerate(br.products):
+            want = np.ldexp(Pref.astype(np.float64), -2 * plan.b).astype(np.float32).T     # (n, m)
+            assert np.array_equal(Pn[t, z], want), (t, z)
+    ws.close()
+
+
+DGEMM_CASES = [
+    # fmt, m, n, k, k_block, s, phi
+    ("fp8", 256, 256, 256, 0, 12, 0.5),          # the small benchmark configuration
+    ("fp8", 300, 270, 520, 0, 15, 4.0),          # ragged, wide exponent range
+    ("fp8", 100, 600, 1000, 384, 12, 2.0),       # k-blocked, short last block
+    ("fp16", 260, 130, 1100, 512, 7, 1.0),
+    ("fp16", 512, 256, 2048, 1024, 8, 1.0),
+    ("fp8", 513, 255, 2048, 0, 13, 1.0),
+    ("fp8", 16, 16, 16, 0, 3, 1.0),
+]
+
+
+@pytest.mark.parametrize("fmt,m,n,k,k_block,s,phi", DGEMM_CASES)
+@pytest.mark.parametrize("accum", ["hw", "emu"])
+def test_dgemm_matches_oracle(fmt, m, n, k, k_block, s, phi, accum):
+    A, B = inputs.phi_pair(m, n, k, phi, seed=7 * m + n + k)
+    Ad, Bd = _upload(A, B)
+    ldc = m + 3
+    Cd = torch.full((n, ldc), float("nan"), dtype=torch.float64, device="cuda")
+    ws = device.Workspace.for_problem(m, n, k, FMT[fmt], s, k_block)
+    lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, ldc, FMT[fmt], s, k_block, ACC[accum])
+    assert lib.ozaki_last_device_status() == 0
+    Cfull = Cd.cpu().numpy()
+    C = Cfull[:, :m].T
+    assert np.all(np.isnan(Cfull[:, m:]))                         # the padding of ldc is not touched
+    Cref = oz.ozaki_dgemm(A, B, fmt, s, k_block)
+    assert np.array_equal(C.view(np.uint64), Cref.view(np.uint64))
+    # the stated bound against the exact product, on sampled entries, next to a native FP64 GEMM
+    ent = exact.sample_entries(m, n, 12, seed=m)
+    e_ab, e_c, _, _ = exact.sampled_errors(A, B, ent, [C[i, j] for i, j in ent])
+    if s >= 7:
+        assert e_ab <= 4 * k * 2.0 ** -53
+    ws.close()
+
+
+def test_chunked_workspace_gives_identical_bits():
+    fmt, m, n, k, s = "fp8", 300, 270, 520, 8
+    A, B = inputs.phi_pair(m, n, k, 1.0, seed=5)
+    Ad, Bd = _upload(A, B)
+    outs = []
+    for minimum in (False, True):
+        ws = device.Workspace.for_problem(m, n, k, FMT[fmt], s, 0, minimum=minimum)
+        for accum in ("hw", "emu"):
+            Cd = torch.zeros((n, m), dtype=torch.float64, device="cuda")
+            lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, FMT[fmt], s, 0, ACC[accum])
+            torch.cuda.synchronize()
+            outs.append(Cd.cpu().numpy().view(np.uint64))
+        ws.close()
+    assert all(np.array_equal(outs[0], o) for o in outs[1:])
+    # and repeated runs are reproducible bit for bit
+    ws = device.Workspace.for_problem(m, n, k, FMT[fmt], s, 0)
+    Cd = torch.zeros((n, m), dtype=torch.float64, device="cuda")
+    lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, FMT[fmt], s, 0, ACC["hw"])
+    assert np.array_equal(Cd.cpu().numpy().view(np.uint64), outs[0])
+    ws.close()
+
+
+def test_emulated_add_is_bitwise_hardware_on_device():
+    rng = np.random.default_rng(77)
+    n = 4_000_000
+
+    def rnd(n, lo, hi):
+        frac = rng.integers(0, 1 << 52, n, dtype=np.uint64)
+        e = rng.integers(lo + 1023, hi + 1023, n, dtype=np.uint64)
+        sg = rng.integers(0, 2, n, dtype=np.uint64)
+        return ((sg << np.uint64(63)) | (e << np.uint64(52)) | frac).view(np.float64)
+
+    a = rnd(3 * n, -300, 300)
+    b = np.concatenate([
+        rnd(n, -300, 300),
+        np.ldexp(rnd(n, -1, 1), np.frexp(a[n:2 * n])[1] + rng.integers(-70, 71, n)),
+        -a[2 * n:] * (1.0 + np.ldexp(rng.integers(-8, 9, n).astype(np.float64), -rng.integers(30, 53, n))),
+    ])
+    a[:4] = [0.0, 1.5, 0.0, -2.5]
+    b[:4] = [0.0, 0.0, -3.0, 2.5]
+    ad, bd = torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda()
+    out = torch.empty_like(ad)
+    lib.ozaki_set_stream(torch.cuda.current_stream().cuda_stream)
+    lib.ozaki_fp64_add_emulated(ad, bd, out, a.size)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.array_equal(got.view(np.uint64), (a + b).view(np.uint64))
+    assert np.array_equal(got.view(np.uint64), (ad + bd).cpu().numpy().view(np.uint64))     # the GPU's own FP64 adder
+
+
+def test_edge_cases_and_error_paths():
+    m, n, k = 48, 32, 64
+    A, B = inputs.phi_pair(m, n, k, 1.0, seed=1)
+    Ad, Bd = _upload(A, B)
+    Cd = torch.full((n, m), 7.0, dtype=torch.float64, device="cuda")
+    ws = device.Workspace.for_problem(m, n, k, 0, 4, 0)
+    # empty problems succeed and leave C alone; k = 0 zeroes C
+    assert lib.ozaki_dgemm(0, n, k, Ad, 1, Bd, k, Cd, 1, 0, 4, 0, 0) == 0
+    assert lib.ozaki_dgemm(m, 0, k, Ad, m, Bd, k, Cd, m, 0, 4, 0, 0) == 0
+    torch.cuda.synchronize()
+    assert float(Cd.min()) == 7.0
+    assert lib.ozaki_dgemm(m, n, 0, Ad, m, Bd, 1, Cd, m, 0, 4, 0, 0) == 0
+    torch.cuda.synchronize()
+    assert float(Cd.abs().max()) == 0.0
+    # argument errors: nothing is launched
+    assert lib.ozaki_dgemm(-1, n, k, Ad, m, Bd, k, Cd, m, 0, 4, 0, 0, check=False) == -1
+    assert lib.ozaki_dgemm(m, n, k, Ad, m - 1, Bd, k, Cd, m, 0, 4, 0, 0, check=False) == -5
+    assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k - 1, Cd, m, 0, 4, 0, 0, check=False) == -7
+    assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m - 1, 0, 4, 0, 0, check=False) == -9
+    assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 2, 4, 0, 0, check=False) == -10
+    assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 0, 4, 0, 2, check=False) == -13
+    assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 0, 33, 0, 0, check=False) == lib.STATUS_INFEASIBLE
+    # workspace too small
+    ws.close()
+    small = device.Workspace(4096)
+    assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 0, 4, 0, 0, check=False) == lib.STATUS_WORKSPACE
+    small.close()
+    assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 0, 4, 0, 0, check=False) == lib.STATUS_WORKSPACE
+    # non-finite input raises the device flag once
+    ws = device.Workspace.for_problem(m, n, k, 0, 4, 0)
+    A2 = A.copy()
+    A2[3, 5] = np.inf
+    A2d = device.to_device_colmajor(A2)
+    lib.ozaki_dgemm(m, n, k, A2d, m, Bd, k, Cd, m, 0, 4, 0, 0)
+    assert lib.ozaki_last_device_status() == lib.STATUS_NONFINITE
+    lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 0, 4, 0, 0)
+    assert lib.ozaki_last_device_status() == 0
+    # default number of slices (data-independent heuristic; parity unpinned): still inside the bound
+    lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 0, 0, 0, 0)
+    torch.cuda.synchronize()
+    C = device.from_device_colmajor(Cd)
+    ent = exact.sample_entries(m, n, 10, seed=2)
+    assert exact.sampled_errors(A, B, ent, [C[i, j] for i, j in ent])[0] <= 4 * k * 2.0 ** -53
+    ws.close()
+
+
+def test_one_slice_integer_inputs_reproduce_integer_gemm():
+    rng = np.random.default_rng(3)
+    m, n, k = 70, 90, 200
+    QA = rng.integers(-16, 17, (m, k))
+    QB = rng.integers(-16, 17, (k, n))
+    QA[:, 0] = 16
+    QB[0, :] = -16
+    A = np.ldexp(QA.astype(np.float64), rng.integers(-20, 20, m)[:, None])
+    B = np.ldexp(QB.astype(np.float64), rng.integers(-20, 20, n)[None, :])
+    Ad, Bd = _upload(A, B)
+    Cd = torch.zeros((n, m), dtype=torch.float64, device="cuda")
+    ws = device.Workspace.for_problem(m, n, k, 0, 1, 0)
+    for accum in (0, 1):
+        lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 0, 1, 0, accum)
+        torch.cuda.synchronize()
+        assert np.array_equal(device.from_device_colmajor(Cd), A @ B)       # A @ B is exact here
+    ws.close()
+
+
+@pytest.mark.parametrize("name", ["c2_4096_fp8_hw", "c3_8192_fp8_emu"])
+def test_full_size_configs_on_sampled_rows_and_columns(name):
+    """At the benchmark's sizes the oracle cannot form all of C; rows of A and columns of B are sliced
+    independently of each other, so the oracle run on a few rows and columns must reproduce exactly the
+    corresponding entries of the device result, and its slices the corresponding device slices."""
+    cfg = inputs.CONFIGS[name]
+    m, n, k, fmt, kb = cfg["m"], cfg["n"], cfg["k"], cfg["fmt"], cfg["k_block"]
+    s = 13 if name.startswith("c2") else 16
+    A, B = inputs.phi_pair(m, n, k, cfg["phi"], seed=0)
+    Ad, Bd = _upload(A, B)
+    Cd = torch.empty((n, m), dtype=torch.float64, device="cuda")
+    ws = device.Workspace.for_problem(m, n, k, FMT[fmt], s, kb)
+    lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, FMT[fmt], s, kb, ACC[cfg["accum"]])
+    assert lib.ozaki_last_device_status() == 0
+    rng = np.random.default_rng(42)
+    rows = np.sort(rng.choice(m, 24, replace=False))
+    cols = np.sort(rng.choice(n, 24, replace=False))
+    rows[0], cols[-1] = 0, n - 1
+    Csub = Cd[torch.from_numpy(cols).cuda()][:, torch.from_numpy(rows).cuda()].cpu().numpy().T
+    Cref = oz.ozaki_dgemm(A[rows, :], B[:, cols], fmt, s, kb)
+    assert np.array_equal(Csub.view(np.uint64), Cref.view(np.uint64))
+    ent = [(int(rows[i]), int(cols[j])) for i, j in zip(rng.integers(0, 24, 16), rng.integers(0, 24, 16))]
+    got = [Csub[list(rows).index(i), list(cols).index(j)] for i, j in ent]
+    e_ab, e_c, _, _ = exact.sampled_errors(A, B, ent, got)
+    assert e_ab <= 4 * k * 2.0 ** -53
+    ws.close()
+    del Cd, ws
+    torch.cuda.empty_cache()
