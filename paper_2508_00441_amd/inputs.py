@@ -57,3 +57,17 @@ CONFIGS = {
     "c5a_16384x1024_fp8":   dict(m=16384, n=16384, k=1024,  phi=2.0, fmt="fp8",  k_block=1024, accum="emu"),
     "c5b_1024x65536_fp8":   dict(m=1024,  n=1024,  k=65536, phi=2.0, fmt="fp8",  k_block=8192, accum="emu"),
 }
+
+#: Slices per configuration for full FP64 accuracy (error no larger than a plain FP64 GEMM on the same
+#: entries): the s_native column of tests/golden/slices_per_config.txt.  S_BOUND is the smallest count
+#: that meets the componentwise bound 4 k 2^-53.
+NUM_SLICES = {
+    "c1_256_fp8_hw": 12, "c2_4096_fp8_hw": 13, "c3_8192_fp8_emu": 16,
+    "c4_16384_fp16_kb1024": 8, "c4_16384_fp16_kb4096": 9, "c4_16384_fp8": 13,
+    "c5a_16384x1024_fp8": 13, "c5b_1024x65536_fp8": 13,
+}
+S_BOUND = {
+    "c1_256_fp8_hw": 10, "c2_4096_fp8_hw": 10, "c3_8192_fp8_emu": 13,
+    "c4_16384_fp16_kb1024": 6, "c4_16384_fp16_kb4096": 7, "c4_16384_fp8": 9,
+    "c5a_16384x1024_fp8": 11, "c5b_1024x65536_fp8": 10,
+}

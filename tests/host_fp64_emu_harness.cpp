@@ -1,0 +1,15 @@
+// Host build of the product's integer-only FP64 routines, for CPU-side unit tests (no GPU involved).
+#include "../paper_2508_00441_amd/csrc/fp64_emu.hpp"
+#include <stddef.h>
+
+extern "C" {
+void host_fp64_add_emulated(const uint64_t* a, const uint64_t* b, uint64_t* out, size_t n) {
+    for (size_t i = 0; i < n; ++i) out[i] = ozaki::fp64_add_emulated(a[i], b[i]);
+}
+void host_fp32_scaled_to_fp64(const uint32_t* f, const int* e2, uint64_t* out, size_t n) {
+    for (size_t i = 0; i < n; ++i) out[i] = ozaki::fp32_bits_scaled_to_fp64(f[i], e2[i]);
+}
+void host_fp64_scale_pow2(const uint64_t* x, const int* e2, uint64_t* out, size_t n) {
+    for (size_t i = 0; i < n; ++i) out[i] = ozaki::fp64_scale_pow2_emulated(x[i], e2[i]);
+}
+}

@@ -1,0 +1,139 @@
+"""Host-side checks of the product that need no GPU: the C-ABI library loads and exports every symbol the
+header declares, the host planner agrees with the oracle's constants, and the integer-only FP64 routines
+(compiled for the host) agree with the host FPU."""
+import ctypes
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+from oracle import ozaki_oracle as oz
+from paper_2508_00441_amd import binding as lib
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    if not os.path.exists(lib.LIB_PATH):
+        from paper_2508_00441_amd import build
+        build.build_library(verbose=False)
+    lib.load()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ozaki_dgemm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ozaki_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert len(names) >= 14
+    raw = ctypes.CDLL(lib.LIB_PATH)
+    for name in names:
+        assert hasattr(raw, name), name
+    assert sorted(lib.SIGNATURES) == names           # the binding covers the same set, no more, no less
+
+
+def test_planner_matches_eq_1_to_3():
+    for fmt, fid in (("fp8", lib.SLICE_FP8_E4M3), ("fp16", lib.SLICE_FP16)):
+        for k in [1, 2, 3, 8, 16, 17, 64, 65, 255, 256, 1024, 1025, 4096, 5000, 16384, 16385, 65536, 65537, 262144, 1 << 24]:
+            p = oz.make_plan(k, fmt)
+            assert lib.ozaki_plan(k, fid) == (p.rho, p.b), (fmt, k)
+    with pytest.raises(lib.OzakiError) as e:
+        lib.ozaki_plan((1 << 24) + 1, lib.SLICE_FP8_E4M3)
+    assert e.value.status == lib.STATUS_INFEASIBLE
+    with pytest.raises(lib.OzakiError) as e:
+        lib.ozaki_plan(0, 0)
+    assert e.value.status == -1
+    with pytest.raises(lib.OzakiError) as e:
+        lib.ozaki_plan(16, 7)
+    assert e.value.status == -2
+
+
+def test_workspace_sizes():
+    full = lib.ozaki_workspace_bytes(8192, 8192, 8192, 0, 16, 0)
+    mini = lib.ozaki_workspace_min_bytes(8192, 8192, 8192, 0, 16, 0)
+    pair = 8192 * 8192 * 4
+    slices = 2 * 16 * 8192 * 8192
+    assert full >= 136 * pair + slices + 8192 * 8192 * 8
+    assert slices + 8192 * 8192 * 8 + pair < mini < full
+    # more pairs than the resident-product budget: capped, with room for the running FP64 sum
+    big = lib.ozaki_workspace_bytes(16384, 16384, 16384, 0, 13, 0)
+    assert big < (64 << 30) + 2 * 13 * 16384 * 16384 + 3 * 16384 * 16384 * 8 + (1 << 20)
+    assert lib.ozaki_workspace_bytes(16, 16, 16, 5, 4, 0) == 0          # bad format
+    assert lib.ozaki_workspace_bytes(16, 16, 1 << 20, 0, 4, 0) == 0     # block longer than the library supports
+    assert lib.ozaki_workspace_bytes(16, 16, 1 << 20, 0, 4, 8192) > 0
+    assert lib.ozaki_workspace_bytes(0, 0, 0, 0, 4, 0) >= 256
+
+
+def test_argument_errors_are_reported_before_anything_is_launched():
+    f = lib.load().ozaki_dgemm
+    assert f(-1, 1, 1, None, 1, None, 1, None, 1, 0, 4, 0, 0) == -1
+    assert f(1, -1, 1, None, 1, None, 1, None, 1, 0, 4, 0, 0) == -2
+    assert f(1, 1, -1, None, 1, None, 1, None, 1, 0, 4, 0, 0) == -3
+    assert f(1, 1, 1, None, 1, None, 1, None, 1, 9, 4, 0, 0) == -10
+    assert f(1, 1, 1, None, 1, None, 1, None, 1, 0, -4, 0, 0) == -11
+    assert f(1, 1, 1, None, 1, None, 1, None, 1, 0, 4, -1, 0) == -12
+    assert f(1, 1, 1, None, 1, None, 1, None, 1, 0, 4, 0, 5) == -13
+    assert f(1, 1, 1, None, 1, None, 1, None, 1, 0, 4, 0, 0) == -8       # C missing
+    assert f(1, 1, 1, None, 1, None, 1, 1 << 20, 1, 0, 4, 0, 0) == -4    # A missing
+    assert f(1, 1, 70000, None, 1, None, 1, None, 1, 0, 4, 0, 0) == lib.STATUS_INFEASIBLE
+    assert f(0, 0, 5, None, 1, None, 1, None, 1, 0, 4, 0, 0) == 0        # empty product: nothing to do
+    assert "workspace" in lib.status_string(lib.STATUS_WORKSPACE)
+    assert "argument" in lib.status_string(-3)
+
+
+@pytest.fixture(scope="module")
+def host_emu(tmp_path_factory):
+    out = tmp_path_factory.mktemp("emu") / "libhostemu.so"
+    subprocess.check_call(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-o", str(out),
+                           os.path.join(ROOT, "tests", "host_fp64_emu_harness.cpp")])
+    return ctypes.CDLL(str(out))
+
+
+def _rnd(rng, n, lo, hi):
+    frac = rng.integers(0, 1 << 52, n, dtype=np.uint64)
+    e = rng.integers(lo + 1023, hi + 1023, n, dtype=np.uint64)
+    sg = rng.integers(0, 2, n, dtype=np.uint64)
+    return ((sg << np.uint64(63)) | (e << np.uint64(52)) | frac).view(np.float64)
+
+
+def test_product_fp64_add_emulation_on_host_equals_fpu(host_emu):
+    rng = np.random.default_rng(5)
+    n = 1_000_000
+    a = _rnd(rng, 4 * n, -300, 300)
+    ulp = np.ldexp(1.0, np.frexp(a[3 * n:])[1] - 53)
+    b = np.concatenate([
+        _rnd(rng, n, -300, 300),
+        np.ldexp(_rnd(rng, n, -1, 1), np.frexp(a[n:2 * n])[1] + rng.integers(-70, 71, n)),
+        -a[2 * n:3 * n] * (1.0 + np.ldexp(rng.integers(-8, 9, n).astype(np.float64), -rng.integers(30, 53, n))),
+        ulp * rng.choice([0.5, -0.5, 1.5, -1.5, 0.25, -0.25, 0.75], n),
+    ])
+    a[:5] = [0.0, -0.0, 1.5, 0.0, -2.5]
+    b[:5] = [-0.0, -0.0, 0.0, -3.0, 2.5]
+    out = np.empty_like(a)
+    host_emu.host_fp64_add_emulated(a.ctypes.data_as(ctypes.c_void_p), b.ctypes.data_as(ctypes.c_void_p),
+                                    out.ctypes.data_as(ctypes.c_void_p), ctypes.c_size_t(a.size))
+    assert np.array_equal(out.view(np.uint64), (a + b).view(np.uint64))
+
+
+def test_product_fp32_to_fp64_scaling_on_host(host_emu):
+    rng = np.random.default_rng(6)
+    n = 500_000
+    f = np.ldexp(rng.integers(-(1 << 24), (1 << 24) + 1, n).astype(np.float32), -8)
+    e2 = rng.integers(-300, 300, n).astype(np.int32)
+    out = np.empty(n, dtype=np.uint64)
+    host_emu.host_fp32_scaled_to_fp64(f.ctypes.data_as(ctypes.c_void_p), e2.ctypes.data_as(ctypes.c_void_p),
+                                      out.ctypes.data_as(ctypes.c_void_p), ctypes.c_size_t(n))
+    want = np.ldexp(f.astype(np.float64), e2)
+    want = np.where(f == 0, 0.0, want)
+    assert np.array_equal(out, want.view(np.uint64))
+    x = want
+    out2 = np.empty(n, dtype=np.uint64)
+    host_emu.host_fp64_scale_pow2(x.ctypes.data_as(ctypes.c_void_p), e2.ctypes.data_as(ctypes.c_void_p),
+                                  out2.ctypes.data_as(ctypes.c_void_p), ctypes.c_size_t(n))
+    assert np.array_equal(out2, np.ldexp(x, e2).view(np.uint64))
