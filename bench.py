@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--accum", choices=["hw", "emu"], default=None, help="override the configuration's accumulation mode")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sample", type=int, default=0, help="rows/columns of the CPU-oracle sample (0: sized for ~15 s)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one elementwise FP32 pass over 1 GiB (reads 1 GiB, writes 1 GiB) before the timed "
+                         "region, so that a counter run can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
     return ap.parse_args()
 
 
@@ -121,6 +124,12 @@ def main():
     def step():
         lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, fmt_id, s, kb, acc_id)
 
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -164,7 +173,7 @@ def main():
         "mfma_frac_of_total_time": pairs * flop / sec_per_step / 1e12 / peak,
     }
     if not args.no_cpu_baseline:
-        sample = args.sample or {256: 256, 4096: 448, 8192: 384}.get(k, 256)
+        sample = args.sample or {256: 256, 1024: 1024, 4096: 1024, 8192: 1024, 16384: 768, 65536: 512}.get(k, 256)
         out.update(cpu_baseline_leg(cfg, s, A, B, Cd, sample))
     ws.close()
     print(json.dumps(out))
