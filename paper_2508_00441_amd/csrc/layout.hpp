@@ -12,12 +12,12 @@ constexpr int64_t MAX_K_BLOCK = 32768;
 
 // ---- tiling of the slice-pair GEMM: one workgroup computes one TILE x TILE block of one pair product ------
 constexpr int TILE = 256;
-constexpr int CHUNK_BYTES = 128;          // bytes of the inner dimension per row staged per pipeline step
+constexpr int CHUNK_BYTES = 64;           // bytes of the inner dimension per row staged per pipeline step
 constexpr int TILE_ELEMS = TILE * TILE;
 
 // ---- slice storage ---------------------------------------------------------------------------------------
 // One slice matrix (block t, slice p) of an operand is stored as [chunk kc][vector r][CHUNK_BYTES]:
-// the 256 vectors a workgroup stages for one pipeline step are 32 KiB of contiguous memory.  The number
+// the 256 vectors a workgroup stages for one pipeline step are 16 KiB of contiguous memory.  The number
 // of vectors is padded to a multiple of TILE and every block to whole chunks; the padding holds zero
 // codes, which contribute exact zeros to every product.
 struct Operand {
