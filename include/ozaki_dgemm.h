@@ -77,7 +77,10 @@ int ozaki_plan(int64_t k_block, int slice_format, int* rho_out, int* bits_out);
  *                 must not overlap A, B or the workspace
  *   slice_format  OZAKI_SLICE_*
  *   num_slices    s >= 1: number of slices taken from every row of A and every column of B (Eq. 4-8);
- *                 the slice pairs (p, q) with p + q <= s + 1 are multiplied (s(s+1)/2 products).
+ *                 the slice pairs (p, q) with p + q <= s + 1 are multiplied (s(s+1)/2 products) and
+ *                 accumulated anti-diagonal by anti-diagonal, least significant first; products of one
+ *                 anti-diagonal that carry the same power-of-two scale for an element are summed exactly
+ *                 before the (rounded) FP64 addition.
  *                 0 selects a data-independent default (ceil(61 / (b+1)) slices).
  *   k_block       inner-product-wise block length (Section 4.3); 0 means k (no blocking).  A last,
  *                 shorter block is allowed.  Must not exceed OZAKI_MAX_K_BLOCK elements.
@@ -100,7 +103,8 @@ int ozaki_set_stream(void* hip_stream);
  *   ozaki_workspace_bytes      size that lets ozaki_dgemm keep all s(s+1)/2 pair products of one block
  *                              resident (capped at 64 GiB of products; more pairs are then processed in
  *                              several passes).  0 if the arguments are invalid or infeasible.
- *   ozaki_workspace_min_bytes  smallest size ozaki_dgemm accepts (one pair product resident at a time).
+ *   ozaki_workspace_min_bytes  smallest size ozaki_dgemm accepts (the s products of the longest anti-diagonal
+ *                              resident at a time).
  *   ozaki_set_workspace        dev_ptr: DEVICE memory, 256-byte aligned, owned by the caller, must stay
  *                              valid until replaced; bytes: its size.  (NULL, 0) clears it.
  */

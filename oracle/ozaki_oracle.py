@@ -15,7 +15,8 @@ Conventions (this build's readings of points the paper leaves open are listed in
   * Eq. 4's ceil(log2(max)) is evaluated exactly: the smallest integer c with max <= 2^c; c = 0 for a zero vector.
   * With num_slices = s on both operands the pairs used are those with p + q <= s + 1 ("triangle"),
     or all s*s ("full").  Accumulation order: anti-diagonals g = p+q from the largest g (smallest
-    magnitude) down to 2, p ascending inside an anti-diagonal.
+    magnitude) down to 2, p ascending inside an anti-diagonal.  Products of one anti-diagonal that carry
+    the same scale factor for an element are summed exactly first (see `block_result`).
 """
 from __future__ import annotations
 
@@ -201,31 +202,65 @@ class BlockResult:
     S: np.ndarray                   # FP64 block sum
 
 
+def run_limit(plan: Plan) -> int:
+    """How many slice-pair products of one block may be summed in Type3 = FP32 without leaving the exact
+    window of Eq. 11: every product is at most k_block * 4^b units of 2^-2b, the window is 2^24 units."""
+    return max(1, (1 << M_FP32) // (plan.k_block << (2 * plan.b)))
+
+
 def block_result(Ab: np.ndarray, Bb: np.ndarray, plan: Plan, num_slices: int, mode: str = "triangle",
-                 add: Callable = hw_add, keep: bool = True) -> BlockResult:
-    """One k-block: slice rows of Ab (m x kb) and columns of Bb (kb x n), form the pair products, accumulate."""
+                 add: Callable = hw_add, keep: bool = True, group: bool = True) -> BlockResult:
+    """One k-block: slice rows of Ab (m x kb) and columns of Bb (kb x n), form the pair products, accumulate.
+
+    Accumulation (element by element): the pairs are visited in `pair_order`.  With `group` set, every
+    anti-diagonal is cut into consecutive chunks of `run_limit` pairs; inside a chunk, consecutive pairs
+    whose scale factor 2^(c_x+c_y) is the same for that element are first summed exactly (an integer sum
+    that would also be exact in FP32, Eq. 11) and each such run is then added with one FP64 addition.
+    Without `group` every product is added on its own.
+    """
     sa, ca, _ = slice_rows(Ab, plan.rho, num_slices)
     sb, cb, _ = slice_rows(np.ascontiguousarray(Bb.T), plan.rho, num_slices)
     qa = [slice_integers(s_, plan.b) for s_ in sa]
     qb = [slice_integers(s_, plan.b) for s_ in sb]
     limit = 1 << M_FP32
-    S = np.zeros((Ab.shape[0], Bb.shape[1]), dtype=np.float64)
+    shape = (Ab.shape[0], Bb.shape[1])
+    S = np.zeros(shape, dtype=np.float64)
     pairs = pair_order(num_slices, mode)
     products = []
+    gmax = run_limit(plan) if group else 1
+    run_sum = np.zeros(shape, dtype=np.int64)          # exact sum of the current run, in units of 2^(run_e)
+    run_e = np.zeros(shape, dtype=np.int64)
+    open_run = np.zeros(shape, dtype=bool)
+    run_diag, pos = None, 0                            # anti-diagonal of the previous pair, position inside it
+
+    def flush(mask):
+        nonlocal S
+        term = np.where(mask, np.ldexp(run_sum.astype(np.float64), run_e), 0.0)   # exact: |run_sum| <= 2^24
+        S = add(S, term)                                                           # adding +0.0 changes nothing
+
     for (p, q) in pairs:
         P = pair_product_int(qa[p - 1], qb[q - 1])
         if P.size and np.max(np.abs(P)) > limit:
             raise AssertionError("pair product exceeds the exact FP32 range (Eq. 11 violated)")
-        e = (ca[p - 1][:, None] + cb[q - 1][None, :] - 2 * plan.b).astype(np.int64)
-        term = np.ldexp(P.astype(np.float64), e)                 # 2^(c_x+c_y) * product, exact
-        S = add(S, term)
+        e = (ca[p - 1][:, None] + cb[q - 1][None, :] - 2 * plan.b).astype(np.int64)   # 2^(c_x+c_y) * 2^-2b
+        pos = pos + 1 if run_diag == p + q else 0
+        run_diag = p + q
+        inside_chunk = pos % gmax != 0                 # a chunk boundary (or a new anti-diagonal) ends every run
+        cont = open_run & inside_chunk & (e == run_e)
+        flush(open_run & ~cont)
+        run_sum = np.where(cont, run_sum + P, P)
+        run_e = e
+        open_run = np.ones(shape, dtype=bool)
+        if run_sum.size and np.max(np.abs(run_sum)) > limit:
+            raise AssertionError("a run of pair products exceeds the exact FP32 range")
         if keep:
             products.append(P)
+    flush(open_run)
     return BlockResult(sa, sb, ca, cb, pairs, products, S)
 
 
 def ozaki_dgemm(A: np.ndarray, B: np.ndarray, fmt: str = "fp8", num_slices: int = 11, k_block: int = 0,
-                mode: str = "triangle", add: Callable = hw_add, return_blocks: bool = False):
+                mode: str = "triangle", add: Callable = hw_add, return_blocks: bool = False, group: bool = True):
     """C = A B by the Ozaki scheme with inner-product-wise blocking (Section 4.3): every block's sum is
     formed first, then added to C in FP64, blocks in ascending k."""
     A = np.asarray(A, dtype=np.float64)
@@ -240,7 +275,7 @@ def ozaki_dgemm(A: np.ndarray, B: np.ndarray, fmt: str = "fp8", num_slices: int 
     blocks = []
     for t in range(plan.num_blocks):
         k0, k1 = t * plan.k_block, min(k, (t + 1) * plan.k_block)
-        br = block_result(A[:, k0:k1], B[k0:k1, :], plan, num_slices, mode, add, keep=return_blocks)
+        br = block_result(A[:, k0:k1], B[k0:k1, :], plan, num_slices, mode, add, keep=return_blocks, group=group)
         C = add(C, br.S)
         if return_blocks:
             blocks.append(br)

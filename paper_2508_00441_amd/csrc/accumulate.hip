@@ -1,18 +1,22 @@
 // Accumulation of the slice-pair products into FP64 and the final rescale (paper Section 3, Eq. 10 and the
 // paragraph after Eq. 11; Section 4.2 for the integer-emulated variant; Section 4.3 for the block sum).
 //
-// For one k-block, element (i, j):
-//     S   = sum over the pairs (p, q), least significant anti-diagonal first, of
-//           P_pq(i,j) * 2^((cA_p(i) - cA_1(i)) + (cB_q(j) - cB_1(j)))        each addition rounded to FP64
+// For one k-block, element (i, j), the pairs (p, q) are visited least significant anti-diagonal first, p
+// ascending inside one.  The term of a pair is P_pq(i,j) * 2^e with e = (cA_p(i) - cA_1(i)) + (cB_q(j) - cB_1(j)).
+// Every anti-diagonal is cut into groups of at most run_limit consecutive pairs; inside a group, consecutive
+// pairs with the same e form a run, whose sum stays inside the exact FP32 window of Eq. 11.  A run is summed
+// exactly (a 32-bit integer in units of 2^-2b) and added to the block sum S with ONE rounded FP64 addition.
+// Where a whole group has one scale for every element of a tile, the GEMM kernel has already formed the run's
+// sum in the matrix unit's accumulators and stored it once.  Then
 //     C   = S * 2^(cA_1(i) + cB_1(j))            first block
 //     C  += S * 2^(cA_1(i) + cB_1(j))            later blocks (one more FP64 addition)
 // Scaling by a power of two commutes with rounding (inside the normal range), so summing with exponents
 // relative to the first slice and rescaling once gives the same bits as scaling every term by
 // 2^(cA_p + cB_q) as Eq. 10 writes it.  P_pq is the FP32 value left by the matrix unit; it already
-// contains the factor 2^-2b of the two slice entries.
+// contains the factor 2^-2b of the two slice entries and is an exact integer multiple of 2^-2b.
 //
-// Two instantiations: hardware FP64 (convert, ldexp, add -- no multiply) and integer-only (fp64_emu.hpp),
-// which executes no FP64 instruction at all and returns the same bits.
+// Two instantiations: hardware FP64 (int->double convert, ldexp, add -- no multiply) and integer-only
+// (fp64_emu.hpp), which executes no FP64 instruction at all and returns the same bits.
 //
 // One workgroup handles one 32 x 32 MFMA tile position of a 256 x 256 tile (256 threads x 4 consecutive
 // columns of C each), reading the products in the order the GEMM kernel stored them.
@@ -36,8 +40,13 @@ struct AccArgs {
     int64_t m, n;
     int tiles_m, tiles_n;
     int z0, nz, s;
+    int two_b;               // 2b: the products are integer multiples of 2^-two_b
     int read_S, write_S, add_to_C;
+    int allow_chain;
+    const int32_t* da;       // deltas of the block: [tiles_m][s]
+    const int32_t* db;       // [tiles_n][s]
     PairList pairs;
+    GroupList groups;        // the groups of this launch, in accumulation order
 };
 
 template <bool EMU>
@@ -80,20 +89,46 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
         for (int r = 0; r < 4; ++r) S[r] = 0;
     }
 
-    for (int z = 0; z < a.nz; ++z) {
-        const int p = a.pairs.p[a.z0 + z] - 1, q = a.pairs.q[a.z0 + z] - 1;
-        const uint4 v = *reinterpret_cast<const uint4*>(a.P + (size_t)z * pair_stride + tile_off);
-        const int eA = p == 0 ? 0 : relA[p][ml];
-        const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
+    auto add_run = [&](int r, int run_sum, int run_e) {
+        if (run_sum == 0) return;                                     // adding an exact zero changes nothing
+        if constexpr (EMU) {
+            S[r] = (acc_t)fp64_add_emulated((uint64_t)S[r], int32_scaled_to_fp64(run_sum, run_e - a.two_b));
+        } else {
+            S[r] = (acc_t)((double)S[r] + ldexp((double)run_sum, run_e - a.two_b));
+        }
+    };
+    const int32_t* dA = a.da + (size_t)tm * a.s;
+    const int32_t* dB = a.db + (size_t)tn * a.s;
+    for (int gi = 0; gi < a.groups.ngroups; ++gi) {
+        const int gz = a.groups.z0[gi], glen = a.groups.len[gi];
+        const int p0 = a.pairs.p[gz] - 1, q0 = a.pairs.q[gz] - 1;
+        const float* Pg = a.P + (size_t)(gz - a.z0) * pair_stride + tile_off;
+        // Walk the group run by run: a run is a maximal sequence of pairs linked for this tile, whose exact sum
+        // the GEMM kernel left in the slot of the run's first pair.  Per element, consecutive runs with the same
+        // scale are merged further (32-bit integer, units of 2^-two_b) before the FP64 addition: this is the
+        // element-wise rule "consecutive pairs of a group with equal scale are summed exactly".
+        int run_sum[4] = {0, 0, 0, 0}, run_e[4] = {0, 0, 0, 0};
+        for (int j = 0; j < glen; ++j) {
+            const int p = p0 + j, q = q0 - j;
+            if (j > 0 && a.allow_chain && pair_linked(dA, dB, p - 1, q + 1)) continue;   // inside a stored run
+            const uint4 v = *reinterpret_cast<const uint4*>(Pg + (size_t)j * pair_stride);
+            const int eA = p == 0 ? 0 : relA[p][ml];
+            const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int e = eA + (q == 0 ? 0 : relB[q][nl + r]);
-            if constexpr (EMU) {
-                S[r] = (acc_t)fp64_add_emulated((uint64_t)S[r], fp32_bits_scaled_to_fp64(vv[r], e));
-            } else {
-                S[r] = (acc_t)((double)S[r] + ldexp((double)__uint_as_float(vv[r]), e));
+            for (int r = 0; r < 4; ++r) {
+                const int e = eA + (q == 0 ? 0 : relB[q][nl + r]);
+                const int iv = fp32_bits_to_scaled_int(vv[r], a.two_b);
+                if (j > 0 && e == run_e[r]) {
+                    run_sum[r] += iv;
+                } else {
+                    add_run(r, run_sum[r], run_e[r]);
+                    run_sum[r] = iv;
+                    run_e[r] = e;
+                }
             }
         }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) add_run(r, run_sum[r], run_e[r]);
     }
 
     if (a.write_S) {
@@ -158,7 +193,7 @@ unsigned grid_for(int64_t work_items) {
 }  // namespace
 
 hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B, const PairList& pairs,
-                             int64_t t, int z0, int nz, const float* P, double* S_io,
+                             const GroupList& groups, int64_t t, int z0, int nz, const float* P, double* S_io,
                              double* C, int64_t ldc, int accum_mode, hipStream_t st) {
     if (pl.tiles_m == 0 || pl.tiles_n == 0) return hipSuccess;
     AccArgs a;
@@ -168,6 +203,11 @@ hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B,
     a.rows_pad_a = A.rows_pad; a.rows_pad_b = B.rows_pad;
     a.m = pl.m; a.n = pl.n; a.tiles_m = (int)pl.tiles_m; a.tiles_n = (int)pl.tiles_n;
     a.z0 = z0; a.nz = nz; a.s = pl.s;
+    a.two_b = 2 * pl.b;
+    a.allow_chain = 1;
+    a.da = A.deltas + (size_t)t * pl.tiles_m * pl.s;
+    a.db = B.deltas + (size_t)t * pl.tiles_n * pl.s;
+    a.groups = groups;
     a.read_S = z0 > 0;
     a.write_S = (z0 + nz) < pl.npairs;
     a.add_to_C = t > 0;

@@ -67,6 +67,8 @@ int make_plan(int64_t m, int64_t n, int64_t k, int fmt, int s, int64_t k_block, 
     const int64_t epc = CHUNK_BYTES / pl.elem_bytes;
     pl.chunks = (pl.kb + epc - 1) / epc;
     pl.npairs = pl.s * (pl.s + 1) / 2;
+    pl.run_limit = (int)(((int64_t)1 << 24) / (pl.kb << (2 * pl.b)));
+    if (pl.run_limit < 1) pl.run_limit = 1;
     pl.tiles_m = (m + TILE - 1) / TILE;
     pl.tiles_n = (n + TILE - 1) / TILE;
     pl.m_pad = pl.tiles_m * TILE;
@@ -83,6 +85,22 @@ void make_pairs(int s, PairList& pr) {
         }
 }
 
+// Groups of the pairs [z0, z1): every anti-diagonal is cut into runs of at most run_limit consecutive pairs.
+// [z0, z1) must consist of whole anti-diagonals.
+void make_groups(const Plan& pl, const PairList& pr, int z0, int z1, GroupList& gl) {
+    gl.ngroups = 0;
+    int z = z0;
+    while (z < z1) {
+        const int diag = pr.p[z] + pr.q[z];
+        int len = 1;
+        while (z + len < z1 && len < pl.run_limit && len < 255 && pr.p[z + len] + pr.q[z + len] == diag) ++len;
+        gl.z0[gl.ngroups] = (uint16_t)z;
+        gl.len[gl.ngroups] = (uint8_t)len;
+        ++gl.ngroups;
+        z += len;
+    }
+}
+
 struct Carve {
     int* flags;
     double* At;
@@ -94,9 +112,10 @@ struct Carve {
 
 size_t slices_bytes(const Plan& pl, int64_t rows_pad) { return align_up((size_t)pl.T * pl.s * pl.chunks * rows_pad * CHUNK_BYTES); }
 size_t exps_bytes(const Plan& pl, int64_t rows_pad) { return align_up((size_t)pl.T * pl.s * rows_pad * sizeof(int32_t)); }
+size_t deltas_bytes(const Plan& pl, int64_t rows_pad) { return align_up((size_t)pl.T * (rows_pad / TILE) * pl.s * sizeof(int32_t)); }
 size_t fixed_bytes(const Plan& pl) {
     return FLAG_BYTES + align_up((size_t)pl.m * pl.k * sizeof(double)) + slices_bytes(pl, pl.m_pad) + slices_bytes(pl, pl.n_pad) +
-           exps_bytes(pl, pl.m_pad) + exps_bytes(pl, pl.n_pad);
+           exps_bytes(pl, pl.m_pad) + exps_bytes(pl, pl.n_pad) + deltas_bytes(pl, pl.m_pad) + deltas_bytes(pl, pl.n_pad);
 }
 size_t pair_bytes(const Plan& pl) { return (size_t)pl.m_pad * pl.n_pad * sizeof(float); }
 size_t sum_bytes(const Plan& pl) { return (size_t)pl.m_pad * pl.n_pad * sizeof(double); }
@@ -105,12 +124,14 @@ size_t recommended_bytes(const Plan& pl) {
     const size_t all = (size_t)pl.npairs * pair_bytes(pl);
     if (all <= P_BUDGET) return fixed_bytes(pl) + all;
     size_t fit = P_BUDGET / pair_bytes(pl);
-    if (fit < 1) fit = 1;
+    if (fit < (size_t)pl.s) fit = pl.s;
     return fixed_bytes(pl) + sum_bytes(pl) + fit * pair_bytes(pl);
 }
+// The pair list is processed in passes that end at anti-diagonal boundaries (a run of equal-scale products
+// never spans two passes), so the smallest workspace holds the longest anti-diagonal: s products.
 size_t minimum_bytes(const Plan& pl) {
     if (pl.npairs == 1) return fixed_bytes(pl) + pair_bytes(pl);
-    return fixed_bytes(pl) + sum_bytes(pl) + pair_bytes(pl);
+    return fixed_bytes(pl) + sum_bytes(pl) + (size_t)pl.s * pair_bytes(pl);
 }
 
 // Places every buffer in the workspace; returns false if it does not fit.
@@ -127,6 +148,8 @@ bool carve(const Plan& pl, Carve& c) {
     c.B.slices = g.ws + off; off += slices_bytes(pl, pl.n_pad);
     c.A.exps = reinterpret_cast<int32_t*>(g.ws + off); off += exps_bytes(pl, pl.m_pad);
     c.B.exps = reinterpret_cast<int32_t*>(g.ws + off); off += exps_bytes(pl, pl.n_pad);
+    c.A.deltas = reinterpret_cast<int32_t*>(g.ws + off); off += deltas_bytes(pl, pl.m_pad);
+    c.B.deltas = reinterpret_cast<int32_t*>(g.ws + off); off += deltas_bytes(pl, pl.n_pad);
     if (off > g.ws_bytes) return false;
     const size_t rest = g.ws_bytes - off, pb = pair_bytes(pl);
     if (pb == 0) { c.S = nullptr; c.P = nullptr; c.chunk_pairs = pl.npairs; return true; }
@@ -136,13 +159,28 @@ bool carve(const Plan& pl, Carve& c) {
         c.chunk_pairs = pl.npairs;
         return true;
     }
-    if (rest < sum_bytes(pl) + pb) return false;
+    if (rest < sum_bytes(pl) + (size_t)pl.s * pb) return false;
     c.S = reinterpret_cast<double*>(g.ws + off);
     off += sum_bytes(pl);
     c.P = reinterpret_cast<float*>(g.ws + off);
     size_t fit = (g.ws_bytes - off) / pb;
     c.chunk_pairs = fit > (size_t)pl.npairs ? pl.npairs : (int)fit;
-    return c.chunk_pairs >= 1;
+    return c.chunk_pairs >= pl.s;
+}
+
+// End (exclusive) of the pass that starts at pair z0: as many whole anti-diagonals as fit into `capacity`
+// products.  Anti-diagonal g = s+1 ... 2 has g-1 pairs and the list starts with g = s+1.
+int pass_end(const Plan& pl, int z0, int capacity) {
+    int z = 0, end = z0;
+    for (int gsum = pl.s + 1; gsum >= 2; --gsum) {
+        const int len = gsum - 1;
+        if (z >= z0) {
+            if (z + len - z0 > capacity) break;
+            end = z + len;
+        }
+        z += len;
+    }
+    return end;
 }
 
 // ---- profiling spans -------------------------------------------------------------------------------------------
@@ -172,8 +210,12 @@ int run_split(const Plan& pl, const Carve& c, const double* A, int64_t lda, cons
     if (do_a && pl.m > 0) {
         HIP_TRY(launch_transpose(A, lda, pl.m, pl.k, c.At, g.stream));
         HIP_TRY(launch_split(c.At, pl.k, pl, c.A, c.flags, g.stream));
+        HIP_TRY(launch_deltas(pl, c.A, g.stream));
     }
-    if (do_b && pl.n > 0) HIP_TRY(launch_split(B, ldb, pl, c.B, c.flags, g.stream));
+    if (do_b && pl.n > 0) {
+        HIP_TRY(launch_split(B, ldb, pl, c.B, c.flags, g.stream));
+        HIP_TRY(launch_deltas(pl, c.B, g.stream));
+    }
     return 0;
 }
 
@@ -289,16 +331,19 @@ int ozaki_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, c
     int rc = run_split(pl, c, A, lda, B, ldb, true, true);
     if (rc) return rc;
     for (int64_t t = 0; t < pl.T; ++t) {
-        for (int z0 = 0; z0 < pl.npairs; z0 += c.chunk_pairs) {
-            const int nz = (pl.npairs - z0 < c.chunk_pairs) ? pl.npairs - z0 : c.chunk_pairs;
+        for (int z0 = 0; z0 < pl.npairs;) {
+            const int nz = pass_end(pl, z0, c.chunk_pairs) - z0;
+            GroupList groups;
+            make_groups(pl, pairs, z0, z0 + nz, groups);
             {
                 Phase ph(1);
-                HIP_TRY(launch_pair_gemm(pl, c.A, c.B, pairs, t, z0, nz, c.P, g.stream));
+                HIP_TRY(launch_pair_gemm(pl, c.A, c.B, pairs, groups, true, t, z0, nz, c.P, g.stream));
             }
             {
                 Phase ph(2);
-                HIP_TRY(launch_accumulate(pl, c.A, c.B, pairs, t, z0, nz, c.P, c.S, C, ldc, accum_mode, g.stream));
+                HIP_TRY(launch_accumulate(pl, c.A, c.B, pairs, groups, t, z0, nz, c.P, c.S, C, ldc, accum_mode, g.stream));
             }
+            z0 += nz;
         }
     }
     return 0;
@@ -352,10 +397,13 @@ int ozaki_pair_products(int64_t m, int64_t n, int64_t k, const double* A, int64_
     int rc = run_split(pl, c, A, lda, B, ldb, true, true);
     if (rc) return rc;
     for (int64_t t = 0; t < pl.T; ++t)
-        for (int z0 = 0; z0 < pl.npairs; z0 += c.chunk_pairs) {
-            const int nz = (pl.npairs - z0 < c.chunk_pairs) ? pl.npairs - z0 : c.chunk_pairs;
-            HIP_TRY(launch_pair_gemm(pl, c.A, c.B, pairs, t, z0, nz, c.P, g.stream));
+        for (int z0 = 0; z0 < pl.npairs;) {
+            const int nz = pass_end(pl, z0, c.chunk_pairs) - z0;
+            GroupList groups;
+            make_groups(pl, pairs, z0, z0 + nz, groups);
+            HIP_TRY(launch_pair_gemm(pl, c.A, c.B, pairs, groups, false, t, z0, nz, c.P, g.stream));
             HIP_TRY(launch_export_products(pl, nz, c.P, P_out + ((size_t)t * pl.npairs + z0) * (size_t)m * n, g.stream));
+            z0 += nz;
         }
     return 0;
 }

@@ -25,7 +25,11 @@ struct Operand {
     int64_t rows_pad;     // multiple of TILE
     uint8_t* slices;      // [T][s][chunks][rows_pad][CHUNK_BYTES]
     int32_t* exps;        // [T][s][rows_pad]   exponent c of Eq. 4 (0 for padding vectors)
+    int32_t* deltas;      // [T][rows_pad/TILE][s]  per 256-vector tile and slice p: c_p - c_(p+1) if that difference
+                          //                        is the same for all real vectors of the tile, else DELTA_IRREGULAR
 };
+
+constexpr int DELTA_IRREGULAR = -2147483647 - 1;
 
 struct Plan {
     int64_t m, n, k;
@@ -38,6 +42,7 @@ struct Plan {
     int64_t T;            // number of blocks
     int64_t chunks;       // chunks per block
     int npairs;           // s(s+1)/2
+    int run_limit;        // floor(2^24 / (kb * 4^b)): equal-scale pair products that may be summed exactly in FP32
     int64_t tiles_m, tiles_n;
     int64_t m_pad, n_pad;
 };
@@ -47,6 +52,23 @@ struct PairList {
     uint8_t p[MAX_PAIRS];
     uint8_t q[MAX_PAIRS];
 };
+
+// Consecutive pairs of one anti-diagonal, at most Plan::run_limit of them, never crossing a multiple of run_limit
+// inside the anti-diagonal: the unit whose equal-scale products are summed exactly before the FP64 addition.
+struct GroupList {
+    int ngroups;
+    uint16_t z0[MAX_PAIRS];   // index of the group's first pair in the PairList
+    uint8_t len[MAX_PAIRS];
+};
+
+// True if, for every element of the tile, pair (p+1, q-1) carries the same scale factor 2^(cA + cB) as pair
+// (p, q) (0-based slice indices): then the two products can be summed in the FP32 accumulator of the matrix unit
+// (a group has at most run_limit pairs, so the sum stays inside the exact window).  dA / dB: the tile's rows of
+// Operand::deltas.
+__host__ __device__ inline bool pair_linked(const int32_t* dA, const int32_t* dB, int p, int q) {
+    const int a = dA[p], b = dB[q - 1];
+    return a != DELTA_IRREGULAR && a == b;
+}
 
 // ---- pair-product storage ("accumulator order") ------------------------------------------------------------
 // The FP32 product of one pair is stored tile by tile, [tile_n][tile_m][TILE_ELEMS], and inside a tile in
@@ -72,15 +94,21 @@ hipError_t launch_split(const double* X, int64_t ldv, const Plan& pl, const Oper
 // Internal layout -> plain vector-major codes (verification export).
 hipError_t launch_export_slices(const Plan& pl, const Operand& op, void* out, hipStream_t st);
 
-// Products of pairs [z0, z0+nz) of block t into P ([nz][tiles_n][tiles_m][TILE_ELEMS] floats).
+// Fills Operand::deltas from Operand::exps.
+hipError_t launch_deltas(const Plan& pl, const Operand& op, hipStream_t st);
+
+// Products of the pairs of `groups` (all inside [z0, z0+nz)) of block t into P ([nz][tiles_n][tiles_m][TILE_ELEMS]
+// floats, slot = pair index - z0).  With allow_chain, consecutive pairs of a group that are linked for a tile
+// (pair_linked) form a run whose exact sum is stored in the slot of the run's first pair; the slots of the
+// other pairs of the run are left untouched.
 hipError_t launch_pair_gemm(const Plan& pl, const Operand& A, const Operand& B, const PairList& pairs,
-                            int64_t t, int z0, int nz, float* P, hipStream_t st);
+                            const GroupList& groups, bool allow_chain, int64_t t, int z0, int nz, float* P, hipStream_t st);
 
 // Accumulate pairs [z0, z0+nz) of block t.  S_io: running block sum in accumulator order (read when z0 > 0,
 // written unless the chunk is the block's last one).  On the last chunk the block sum is rescaled by the
 // first-slice exponents and stored to C (t == 0) or added to C (t > 0).
 hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B, const PairList& pairs,
-                             int64_t t, int z0, int nz, const float* P, double* S_io,
+                             const GroupList& groups, int64_t t, int z0, int nz, const float* P, double* S_io,
                              double* C, int64_t ldc, int accum_mode, hipStream_t st);
 
 // P in accumulator order -> [nz][n][m] column-major matrices (verification export).

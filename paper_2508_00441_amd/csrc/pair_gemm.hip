@@ -8,7 +8,9 @@
 // feeds both operands with the same (arbitrary but identical) assignment of inner indices to lanes.
 //
 // Work decomposition: one workgroup of four waves (one per SIMD) computes a 256 x 256 block of P for one
-// pair; each wave owns 128 x 128 (4 x 4 MFMA tiles of 32 x 32, 256 accumulator registers per lane).  The
+// group of pairs (consecutive pairs of an anti-diagonal, streamed through one continuous pipeline; products
+// that carry the same scale factor for the whole tile are summed in the accumulators and stored once, which
+// is exact because a group never exceeds the FP32 window of Eq. 11); each wave owns 128 x 128 (4 x 4 MFMA tiles of 32 x 32, 256 accumulator registers per lane).  The
 // matrix unit's "row" operand is the B slice (index n), its "column" operand the A slice (index m), so that
 // the lanes of a wave run along m, the contiguous direction of column-major C.
 //
@@ -46,8 +48,13 @@ struct GemmArgs {
     int64_t rows_pad_a, rows_pad_b;
     int64_t chunks;
     int tiles_m, tiles_n;
-    int z0;
+    int z0;                  // first pair of this launch: P slot = pair index - z0
+    int s;
+    int allow_chain;
+    const int32_t* da;       // A deltas of the block: [tiles_m][s]
+    const int32_t* db;       // B deltas of the block: [tiles_n][s]
     PairList pairs;
+    GroupList groups;
 };
 
 constexpr int BK = CHUNK_BYTES;                       // bytes of the inner dimension per row and stage
@@ -82,20 +89,33 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wn = wave >> 1, wm = wave & 1;
 
+    // one workgroup = one tile of one group of pairs (p0 + j, q0 - j), j < glen
     const int tiles = a.tiles_m * a.tiles_n;
-    const int zl = blockIdx.x / tiles;
-    const int tile = blockIdx.x - zl * tiles;
+    const int gi = blockIdx.x / tiles;
+    const int tile = blockIdx.x - gi * tiles;
     const int tn = tile / a.tiles_m, tm = tile - tn * a.tiles_m;
-    const int p = a.pairs.p[a.z0 + zl] - 1, q = a.pairs.q[a.z0 + zl] - 1;
+    const int gz = a.groups.z0[gi], glen = a.groups.len[gi];
+    const int p0 = a.pairs.p[gz] - 1, q0 = a.pairs.q[gz] - 1;
     const int chunks = (int)a.chunks;
+    // bit j of `links`: pair j+1 of the group carries, for every element of this tile, the same scale factor as
+    // pair j, so its product keeps accumulating on top of pair j's (the sum stays inside the exact FP32 window
+    // because a group has at most run_limit pairs); otherwise the accumulators are stored and cleared in between
+    unsigned links = 0;
+    if (a.allow_chain) {
+        const int32_t* dA = a.da + (size_t)tm * a.s;
+        const int32_t* dB = a.db + (size_t)tn * a.s;
+        for (int j = 0; j + 1 < glen; ++j) links |= pair_linked(dA, dB, p0 + j, q0 - j) ? (1u << j) : 0u;
+    }
 
     // loader: a wave instruction fills 16 consecutive LDS rows; lane -> row lane/4, physical piece lane%4,
     // which must hold logical piece (lane%4) ^ ((row>>2)&3); the row group starts at a multiple of 16 rows.
     const unsigned lrow = lane >> 2, lpc = lane & 3;
     const unsigned goff = lrow * BK + ((lpc ^ ((lrow >> 2) & 3)) << 4);
     const size_t cs_x = (size_t)a.rows_pad_b * BK, cs_y = (size_t)a.rows_pad_a * BK;
-    const uint8_t* xptr = a.sb + (size_t)q * chunks * cs_x + (size_t)tn * TILE * BK + (size_t)wave * LPW * 1024 + goff;
-    const uint8_t* yptr = a.sa + (size_t)p * chunks * cs_y + (size_t)tm * TILE * BK + (size_t)wave * LPW * 1024 + goff;
+    const uint8_t* const xtile = a.sb + (size_t)tn * TILE * BK + (size_t)wave * LPW * 1024 + goff;
+    const uint8_t* const ytile = a.sa + (size_t)tm * TILE * BK + (size_t)wave * LPW * 1024 + goff;
+    const uint8_t* xptr;
+    const uint8_t* yptr;
 
     // fragments: lane reads row lane%32 of each 32-row MFMA tile; lane/32 selects the k-group
     const int frow = lane & 31, fg = lane >> 5;
@@ -104,16 +124,37 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
     const int ybase = TILE * BK + (wm * 128 + frow) * BK;
 
     v16f acc[4][4];
+    auto zero_acc = [&]() {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    };
+    auto store_acc = [&](int slot) {
+        float* out = a.P + ((size_t)(slot * a.tiles_n + tn) * a.tiles_m + tm) * TILE_ELEMS + (size_t)wave * 16384 + lane * 4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    v4f v = {acc[i][j][4 * g4], acc[i][j][4 * g4 + 1], acc[i][j][4 * g4 + 2], acc[i][j][4 * g4 + 3]};
+                    *reinterpret_cast<v4f*>(out + ((i * 4 + j) * 4 + g4) * 256) = v;
+                }
+    };
 
-    // Fetch the stage xptr/yptr point at into ring buffer `buf`; `advance` moves on to the next chunk.  In the
-    // tail the pointers stay on the last chunk: the (unused) reload keeps the outstanding-load count uniform.
-    auto issue_to = [&](int buf, bool advance) {
+    // The group's pairs are streamed as one sequence of glen * chunks stages.  The A slices p0, p0+1, ... lie back
+    // to back in memory, so yptr simply moves one chunk per stage; the B slices run backwards (q0, q0-1, ...), so
+    // xptr jumps back by two slices minus one chunk when a pair ends.  After the last stage the pointers stay put:
+    // the (unused) reloads keep the outstanding-load count uniform.
+    const int total = glen * chunks;
+    int issued = 0, issue_kc = 0;
+    xptr = xtile + (size_t)q0 * chunks * cs_x;
+    yptr = ytile + (size_t)p0 * chunks * cs_y;
+    const size_t x_wrap = (size_t)(2 * chunks - 1) * cs_x;
+    auto issue_next = [&](int buf) {
         uint8_t* lb = lds + buf * STAGE_BYTES + wave * LPW * 1024;
 #pragma unroll
         for (int i = 0; i < LPW; ++i)
@@ -121,16 +162,22 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
 #pragma unroll
         for (int i = 0; i < LPW; ++i)
             __builtin_amdgcn_global_load_lds(OZAKI_GPTR(yptr + i * 1024), OZAKI_LPTR(lb + TILE * BK + i * 1024), 16, 0, 0);
-        if (advance) {
-            xptr += cs_x;
-            yptr += cs_y;
-        }
+        // branch-free pointer update (a branch here would split the k-step's basic block and with it the
+        // instruction interleaving)
+        const bool adv = issued + 1 < total;
+        const bool wrap = issue_kc + 1 == chunks;
+        const int64_t dx = adv ? (wrap ? -(int64_t)x_wrap : (int64_t)cs_x) : 0;
+        const int64_t dy = adv ? (int64_t)cs_y : 0;
+        xptr += dx;
+        yptr += dy;
+        issued += adv ? 1 : 0;
+        issue_kc = adv ? (wrap ? 0 : issue_kc + 1) : issue_kc;
     };
 
     typedef typename std::conditional<FP16, v8h, v8i>::type frag_t;
     frag_t xf[2][4], yf[2][4];
-    auto read_frags = [&](int kc, int ks, int fb) {
-        const uint8_t* base = lds + (kc % NSTAGE) * STAGE_BYTES;
+    auto read_frags = [&](int stage, int ks, int fb) {
+        const uint8_t* base = lds + ((unsigned)stage % NSTAGE) * STAGE_BYTES;
         if constexpr (FP16) {
             const int c0 = ((2 * ks + fg) ^ fsw) << 4;
 #pragma unroll
@@ -163,25 +210,27 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
             }
     };
 
+    zero_acc();
     // prologue: fill the ring, wait for stage 0, read its first fragments
 #pragma unroll
-    for (int s = 0; s < NSTAGE; ++s) issue_to(s, s + 1 < chunks);
+    for (int st = 0; st < NSTAGE; ++st) issue_next(st);
     wait_and_barrier<(NSTAGE - 1) * 2 * LPW>();
     read_frags(0, 0, 0);
 
     // One k-step: fetch the fragments of the next k-step into the other register buffer, then 16 MFMAs on the
     // current one.  At the last k-step of a stage: every wave waits for its own LDS reads and for the next
     // stage's loads, all waves meet, the next stage's first fragments are read and the dead buffer is refilled.
-    auto kstep = [&](int g, auto fbc) {
+    int stage = 0;
+    auto kstep = [&](auto fbc, auto ksc) {
         constexpr int fb = decltype(fbc)::value;
-        const int kc = g / KS, ks = g % KS;
-        const bool last_of_stage = ks + 1 == KS;
-        if (!last_of_stage) {
-            read_frags(kc, ks + 1, fb ^ 1);
+        constexpr int ks = decltype(ksc)::value;
+        constexpr bool last_of_stage = ks + 1 == KS;
+        if constexpr (!last_of_stage) {
+            read_frags(stage, ks + 1, fb ^ 1);
         } else {
             wait_and_barrier<(NSTAGE - 2) * 2 * LPW>();
-            read_frags(kc + 1 < chunks ? kc + 1 : kc, 0, fb ^ 1);
-            issue_to(kc % NSTAGE, kc + NSTAGE + 1 < chunks);
+            read_frags(stage + 1 < total ? stage + 1 : stage, 0, fb ^ 1);
+            issue_next((unsigned)stage % NSTAGE);
         }
         mfmas(fb);
         // instruction order: the LDS reads behind the first MFMAs (so their latency is covered by the rest of
@@ -192,46 +241,67 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
             if (i < 8) __builtin_amdgcn_sched_group_barrier(0x100, READS / 8, 0);                 // LDS reads
             else if (last_of_stage) __builtin_amdgcn_sched_group_barrier(0x020, 2 * LPW / 8, 0);  // VMEM reads
         }
+        if constexpr (last_of_stage) ++stage;
     };
-    const int ksteps = chunks * KS;
-    int g = 0;
-    for (; g + 1 < ksteps; g += 2) {
-        kstep(g, std::integral_constant<int, 0>());
-        kstep(g + 1, std::integral_constant<int, 1>());
+    const std::integral_constant<int, 0> c0;
+    const std::integral_constant<int, 1> c1;
+    int run_start = 0;
+    for (int jp = 0; jp < glen; ++jp) {
+        if constexpr (KS == 1) {
+            int c = 0;
+            for (; c + 1 < chunks; c += 2) {
+                kstep(c0, c0);
+                kstep(c1, c0);
+            }
+            if (c < chunks) {
+                kstep(c0, c0);
+                // odd number of stages: the fragments just fetched for the next stage sit in buffer 1; the next
+                // k-step reads buffer 0
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    xf[0][i] = xf[1][i];
+                    yf[0][i] = yf[1][i];
+                }
+            }
+        } else {
+            for (int c = 0; c < chunks; ++c) {
+                kstep(c0, c0);
+                kstep(c1, c1);
+            }
+        }
+        // The pair is complete.  If the next pair does not continue the run, store the accumulators to the slot of
+        // the run's first pair and clear them (the stores only make the next vmcnt wait stricter).
+        const bool last_pair = jp + 1 == glen;
+        if (last_pair || !((links >> jp) & 1u)) {
+            store_acc(gz + run_start - a.z0);
+            if (!last_pair) zero_acc();
+            run_start = jp + 1;
+        }
     }
-    if (g < ksteps) kstep(g, std::integral_constant<int, 0>());
 
-    // every direct-to-LDS load (including the tail's unused reloads) must have landed before the workgroup's
-    // LDS allocation is released
+    // every direct-to-LDS load of this wave (including the tail's unused reloads) must have landed before the
+    // workgroup's LDS allocation is released
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
     asm volatile("" ::: "memory");
-
-    float* out = a.P + ((size_t)(zl * a.tiles_n + tn) * a.tiles_m + tm) * TILE_ELEMS + (size_t)wave * 16384 + lane * 4;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                v4f v = {acc[i][j][4 * g4], acc[i][j][4 * g4 + 1], acc[i][j][4 * g4 + 2], acc[i][j][4 * g4 + 3]};
-                *reinterpret_cast<v4f*>(out + ((i * 4 + j) * 4 + g4) * 256) = v;
-            }
 }
 
 }  // namespace
 
 hipError_t launch_pair_gemm(const Plan& pl, const Operand& A, const Operand& B, const PairList& pairs,
-                            int64_t t, int z0, int nz, float* P, hipStream_t st) {
-    if (nz <= 0 || pl.tiles_m == 0 || pl.tiles_n == 0 || pl.chunks == 0) return hipSuccess;
+                            const GroupList& groups, bool allow_chain, int64_t t, int z0, int nz, float* P, hipStream_t st) {
+    if (nz <= 0 || groups.ngroups <= 0 || pl.tiles_m == 0 || pl.tiles_n == 0 || pl.chunks == 0) return hipSuccess;
     GemmArgs a;
     const size_t slice_a = (size_t)pl.chunks * A.rows_pad * CHUNK_BYTES, slice_b = (size_t)pl.chunks * B.rows_pad * CHUNK_BYTES;
     a.sa = A.slices + (size_t)t * pl.s * slice_a;
     a.sb = B.slices + (size_t)t * pl.s * slice_b;
     a.P = P;
     a.rows_pad_a = A.rows_pad; a.rows_pad_b = B.rows_pad; a.chunks = pl.chunks;
-    a.tiles_m = (int)pl.tiles_m; a.tiles_n = (int)pl.tiles_n; a.z0 = z0; a.pairs = pairs;
-    const int64_t blocks = (int64_t)nz * pl.tiles_m * pl.tiles_n;
+    a.tiles_m = (int)pl.tiles_m; a.tiles_n = (int)pl.tiles_n; a.z0 = z0; a.pairs = pairs; a.groups = groups;
+    a.s = pl.s; a.allow_chain = allow_chain ? 1 : 0;
+    a.da = A.deltas + (size_t)t * pl.tiles_m * pl.s;
+    a.db = B.deltas + (size_t)t * pl.tiles_n * pl.s;
+    const int64_t blocks = (int64_t)groups.ngroups * pl.tiles_m * pl.tiles_n;
     if (blocks > 0x7FFFFFFF || pl.chunks > 0x7FFFFFFF) return hipErrorInvalidValue;
     if (pl.fmt == 1) hipLaunchKernelGGL((pair_gemm_kernel<true>), dim3((unsigned)blocks), dim3(256), 0, st, a);
     else hipLaunchKernelGGL((pair_gemm_kernel<false>), dim3((unsigned)blocks), dim3(256), 0, st, a);

@@ -218,6 +218,24 @@ __global__ void __launch_bounds__(256) export_slices_kernel(const uint8_t* __res
     }
 }
 
+// One workgroup per 256-vector tile and block: for every slice p, is c_p - c_(p+1) the same for all real vectors?
+__global__ void __launch_bounds__(256) delta_kernel(const int32_t* __restrict__ exps, int32_t* __restrict__ deltas, int64_t rows,
+                                                    int64_t rows_pad, int s) {
+    __shared__ int ref;
+    const int64_t tile = blockIdx.x, t = blockIdx.y;
+    const int64_t row = tile * TILE + threadIdx.x;
+    const int32_t* e = exps + (size_t)t * s * rows_pad;
+    int32_t* out = deltas + ((size_t)t * gridDim.x + tile) * s;
+    for (int p = 0; p + 1 < s; ++p) {
+        const int d = e[(size_t)p * rows_pad + row] - e[(size_t)(p + 1) * rows_pad + row];
+        if (threadIdx.x == 0) ref = d;               // the first vector of a tile is always a real one
+        __syncthreads();
+        const int same = __syncthreads_and(row >= rows || d == ref);
+        if (threadIdx.x == 0) out[p] = same ? ref : DELTA_IRREGULAR;
+    }
+    if (threadIdx.x == 0) out[s - 1] = DELTA_IRREGULAR;
+}
+
 template <int U, int TPR>
 hipError_t launch_split_cfg(const SplitArgs& a, bool fp16, int64_t T, hipStream_t st) {
     constexpr int BLOCK = TPR < 256 ? 256 : TPR;
@@ -252,6 +270,13 @@ hipError_t launch_split(const double* X, int64_t ldv, const Plan& pl, const Oper
     if (octets <= 2048) return launch_split_cfg<8, 256>(a, fp16, pl.T, st);
     if (octets <= 4096) return launch_split_cfg<4, 1024>(a, fp16, pl.T, st);
     return hipErrorInvalidValue;                                                // the planner rejects longer blocks
+}
+
+hipError_t launch_deltas(const Plan& pl, const Operand& op, hipStream_t st) {
+    if (op.rows == 0 || pl.T == 0) return hipSuccess;
+    hipLaunchKernelGGL(delta_kernel, dim3((unsigned)(op.rows_pad / TILE), (unsigned)pl.T), dim3(256), 0, st, op.exps, op.deltas,
+                       op.rows, op.rows_pad, pl.s);
+    return hipGetLastError();
 }
 
 hipError_t launch_export_slices(const Plan& pl, const Operand& op, void* out, hipStream_t st) {

@@ -252,6 +252,8 @@ def test_edge_cases_and_error_paths():
     lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 0, 4, 0, 0)
     assert lib.ozaki_last_device_status() == 0
     # default number of slices (data-independent heuristic; parity unpinned): still inside the bound
+    ws.close()
+    ws = device.Workspace.for_problem(m, n, k, 0, 0, 0)
     lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 0, 0, 0, 0)
     torch.cuda.synchronize()
     C = device.from_device_colmajor(Cd)
@@ -276,6 +278,27 @@ def test_one_slice_integer_inputs_reproduce_integer_gemm():
         lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 0, 1, 0, accum)
         torch.cuda.synchronize()
         assert np.array_equal(device.from_device_colmajor(Cd), A @ B)       # A @ B is exact here
+    ws.close()
+
+
+def test_products_at_the_edge_of_the_fp32_window():
+    """k_block * 4^b = 2^24 with every entry at the row maximum: each product is exactly +-2^24 units."""
+    m, n, k = 40, 24, 2048
+    A = np.ones((m, k))
+    B = np.ones((k, n))
+    B[:, ::2] = -1.0
+    Ad, Bd = _upload(A, B)
+    Cd = torch.zeros((n, m), dtype=torch.float64, device="cuda")
+    ws = device.Workspace.for_problem(m, n, k, FMT["fp16"], 2, 1024)
+    for accum in (0, 1):
+        lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, FMT["fp16"], 2, 1024, accum)
+        torch.cuda.synchronize()
+        assert np.array_equal(device.from_device_colmajor(Cd), A @ B)
+    P = torch.zeros((2, 3, n, m), dtype=torch.float32, device="cuda")
+    lib.ozaki_pair_products(m, n, k, Ad, m, Bd, k, FMT["fp16"], 2, 1024, P)
+    torch.cuda.synchronize()
+    Pn = P.cpu().numpy()
+    assert np.array_equal(np.abs(Pn[:, 2]), np.full((2, n, m), 1024.0, dtype=np.float32))   # pair (1,1): 2^24 * 2^-14
     ws.close()
 
 

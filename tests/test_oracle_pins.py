@@ -287,6 +287,44 @@ def test_scaling_and_permutation_invariants():
         assert np.array_equal(P4, P.T)
 
 
+def test_equal_scale_runs_are_summed_exactly_before_the_fp64_addition():
+    """Rows/columns inside one binade follow a regular exponent ladder, so every anti-diagonal carries one
+    scale factor; the grouped accumulation must then equal: exact sum of each run of at most run_limit
+    products inside a chunk of run_limit pairs (rational arithmetic here), one FP64 addition per run."""
+    rng = np.random.default_rng(31)
+    m, n, k = 4, 3, 64
+    A = inputs.full_mantissa_one_binade(m, k, rng) * np.where(rng.random((m, k)) < 0.5, -1.0, 1.0)
+    B = (inputs.full_mantissa_one_binade(n, k, rng) * np.where(rng.random((n, k)) < 0.5, -1.0, 1.0)).T.copy()
+    for fmt, kb, s in (("fp8", 0, 7), ("fp16", 16, 4), ("fp8", 16, 6)):
+        plan = oz.make_plan(k, fmt, kb)
+        gmax = oz.run_limit(plan)
+        assert gmax == (1 << 24) // (plan.k_block * 4 ** plan.b)
+        C, blocks = oz.ozaki_dgemm(A, B, fmt, s, kb, return_blocks=True)
+        want = np.zeros((m, n))
+        for br in blocks:
+            S = np.zeros((m, n))
+            for i in range(m):
+                for j in range(n):
+                    run, run_scale, run_open, run_diag, pos, acc = Fraction(0), None, False, None, 0, 0.0
+                    for (p, q), P in zip(br.pairs, br.products):
+                        scale = int(br.c_a[p - 1][i] + br.c_b[q - 1][j])
+                        pos = pos + 1 if p + q == run_diag else 0
+                        if run_open and (scale != run_scale or pos % gmax == 0):
+                            acc = acc + float(run)          # float(Fraction) is exact here: a 25-bit integer times 2^e
+                            run = Fraction(0)
+                        run += Fraction(int(P[i, j])) * Fraction(2) ** (scale - 2 * plan.b)
+                        run_scale, run_diag, run_open = scale, p + q, True
+                    S[i, j] = acc + float(run)
+            want = want + S
+        assert np.array_equal(C.view(np.uint64), want.view(np.uint64)), fmt
+        # the ladder is regular here: fewer FP64 additions than pairs, and never a worse result than pair-by-pair
+        ent = [(i, j) for i in range(m) for j in range(n)]
+        C_plain = oz.ozaki_dgemm(A, B, fmt, s, kb, group=False)
+        e_grouped = exact.sampled_errors(A, B, ent, [C[i, j] for i, j in ent])[0]
+        e_plain = exact.sampled_errors(A, B, ent, [C_plain[i, j] for i, j in ent])[0]
+        assert e_grouped <= e_plain * 1.5 + 2.0 ** -60
+
+
 def test_pair_order_is_least_significant_first():
     assert oz.pair_order(3) == [(1, 3), (2, 2), (3, 1), (1, 2), (2, 1), (1, 1)]
     assert len(oz.pair_order(16)) == 16 * 17 // 2
