@@ -30,6 +30,10 @@ if ROOT not in sys.path:
 
 PEAK_TFLOPS = {"fp8": 5000.0, "fp16": 2500.0}          # MI355X dense MFMA peaks
 DEFAULT_CONFIG = "c3_8192_fp8_emu"                      # the configuration the metric is quoted on (n = 8192)
+# L2-fill + write-back bytes of one pair_gemm_kernel launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script (scaled by the 1 GiB copy-calibration kernel); see profiles/ozaki_dgemm_c3_8192_fp8_emu.md.  Only valid for
+# the configuration's calibrated slice count.
+MEASURED_TRAFFIC_BYTES = {"c3_8192_fp8_emu": 124.04 * 2 ** 30}
 
 
 def parse_args():
@@ -165,7 +169,8 @@ def main():
         },
         "roofline": {
             "kernel": "pair_gemm_kernel", "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-            "frac": achieved / peak, "traffic": None,
+            "frac": achieved / peak,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if not args.num_slices else None, "traffic_unit": "bytes per launch",
             "avg_launch_ms": gemm_launch_ms, "launches_per_step": launches[1] / args.steps,
         },
         "phases_ms_per_step": {"slicing": phase_ms[0] / args.steps, "pair_gemms": phase_ms[1] / args.steps,
@@ -173,7 +178,7 @@ def main():
         "mfma_frac_of_total_time": pairs * flop / sec_per_step / 1e12 / peak,
     }
     if not args.no_cpu_baseline:
-        sample = args.sample or {256: 256, 1024: 1024, 4096: 1024, 8192: 1024, 16384: 768, 65536: 512}.get(k, 256)
+        sample = args.sample or {256: 256, 1024: 2048, 4096: 2048, 8192: 1536, 16384: 1280, 65536: 512}.get(k, 256)
         out.update(cpu_baseline_leg(cfg, s, A, B, Cd, sample))
     ws.close()
     print(json.dumps(out))
