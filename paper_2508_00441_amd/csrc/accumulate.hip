@@ -20,6 +20,8 @@
 //
 // One workgroup handles one 32 x 32 MFMA tile position of a 256 x 256 tile (256 threads x 4 consecutive
 // columns of C each), reading the products in the order the GEMM kernel stored them.
+#include <string.h>
+
 #include <type_traits>
 
 #include "fp64_emu.hpp"
@@ -46,13 +48,15 @@ struct AccArgs {
     const int32_t* da;       // deltas of the block: [tiles_m][s]
     const int32_t* db;       // [tiles_n][s]
     PairList pairs;
-    GroupList groups;        // the groups of this launch, in accumulation order
+    uint8_t first_of_group[MAX_PAIRS];   // per pair of the list: 1 if it opens a group
 };
 
 template <bool EMU>
 __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
     __shared__ int relA[MAX_SLICES][32];
     __shared__ int relB[MAX_SLICES][32];
+    __shared__ uint32_t entries[MAX_PAIRS];           // stored runs of this tile: slot | p << 12 | q << 18 | first-of-group << 24
+    __shared__ int n_entries;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, g4 = tid >> 6;
@@ -89,6 +93,32 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
         for (int r = 0; r < 4; ++r) S[r] = 0;
     }
 
+    // The stored runs of this tile, in accumulation order: a pair starts a run unless it is linked (for the whole
+    // tile) to the pair before it inside its group.  Built by the first wave, 64 pairs at a time.
+    if (tid < 64) {
+        const int32_t* dA = a.da + (size_t)tm * a.s;
+        const int32_t* dB = a.db + (size_t)tn * a.s;
+        int count = 0;
+        for (int base = 0; base < a.nz; base += 64) {
+            const int zl = base + tid;
+            bool start = false;
+            uint32_t entry = 0;
+            if (zl < a.nz) {
+                const int z = a.z0 + zl;
+                const int p = a.pairs.p[z] - 1, q = a.pairs.q[z] - 1;
+                const bool first = a.first_of_group[z] != 0;
+                start = first || !(a.allow_chain && pair_linked(dA, dB, p - 1, q + 1));
+                entry = (uint32_t)zl | ((uint32_t)p << 12) | ((uint32_t)q << 18) | ((uint32_t)first << 24);
+            }
+            const unsigned long long mask = __ballot(start);
+            if (start) entries[count + __popcll(mask & ((1ull << tid) - 1ull))] = entry;
+            count += __popcll(mask);
+        }
+        if (tid == 0) n_entries = count;
+    }
+    __syncthreads();
+    const int n_runs = n_entries;
+
     auto add_run = [&](int r, int run_sum, int run_e) {
         if (run_sum == 0) return;                                     // adding an exact zero changes nothing
         if constexpr (EMU) {
@@ -97,39 +127,46 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
             S[r] = (acc_t)((double)S[r] + ldexp((double)run_sum, run_e - a.two_b));
         }
     };
-    const int32_t* dA = a.da + (size_t)tm * a.s;
-    const int32_t* dB = a.db + (size_t)tn * a.s;
-    for (int gi = 0; gi < a.groups.ngroups; ++gi) {
-        const int gz = a.groups.z0[gi], glen = a.groups.len[gi];
-        const int p0 = a.pairs.p[gz] - 1, q0 = a.pairs.q[gz] - 1;
-        const float* Pg = a.P + (size_t)(gz - a.z0) * pair_stride + tile_off;
-        // Walk the group run by run: a run is a maximal sequence of pairs linked for this tile, whose exact sum
-        // the GEMM kernel left in the slot of the run's first pair.  Per element, consecutive runs with the same
-        // scale are merged further (32-bit integer, units of 2^-two_b) before the FP64 addition: this is the
-        // element-wise rule "consecutive pairs of a group with equal scale are summed exactly".
-        int run_sum[4] = {0, 0, 0, 0}, run_e[4] = {0, 0, 0, 0};
-        for (int j = 0; j < glen; ++j) {
-            const int p = p0 + j, q = q0 - j;
-            if (j > 0 && a.allow_chain && pair_linked(dA, dB, p - 1, q + 1)) continue;   // inside a stored run
-            const uint4 v = *reinterpret_cast<const uint4*>(Pg + (size_t)j * pair_stride);
-            const int eA = p == 0 ? 0 : relA[p][ml];
-            const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
+    // Per element, consecutive stored runs of one group with the same scale are merged further (32-bit integer,
+    // units of 2^-two_b) before the FP64 addition: together with the tile-wide runs formed by the GEMM kernel this
+    // is the element-wise rule "consecutive pairs of a group with equal scale are summed exactly".
+    int run_sum[4] = {0, 0, 0, 0}, run_e[4] = {0, 0, 0, 0};
+    auto process = [&](uint32_t entry, const uint4& v) {
+        const int p = (entry >> 12) & 63, q = (entry >> 18) & 63;
+        const bool first = (entry >> 24) & 1;
+        const int eA = p == 0 ? 0 : relA[p][ml];
+        const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int e = eA + (q == 0 ? 0 : relB[q][nl + r]);
-                const int iv = fp32_bits_to_scaled_int(vv[r], a.two_b);
-                if (j > 0 && e == run_e[r]) {
-                    run_sum[r] += iv;
-                } else {
-                    add_run(r, run_sum[r], run_e[r]);
-                    run_sum[r] = iv;
-                    run_e[r] = e;
-                }
+        for (int r = 0; r < 4; ++r) {
+            const int e = eA + (q == 0 ? 0 : relB[q][nl + r]);
+            const int iv = fp32_bits_to_scaled_int(vv[r], a.two_b);
+            if (!first && e == run_e[r]) {
+                run_sum[r] += iv;
+            } else {
+                add_run(r, run_sum[r], run_e[r]);
+                run_sum[r] = iv;
+                run_e[r] = e;
             }
         }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) add_run(r, run_sum[r], run_e[r]);
+    };
+    auto load_run = [&](int i) -> uint4 {
+        const uint32_t entry = entries[i < n_runs ? i : n_runs - 1];
+        return *reinterpret_cast<const uint4*>(a.P + (size_t)(entry & 0xFFFu) * pair_stride + tile_off);
+    };
+    // four loads in flight per thread
+    if (n_runs > 0) {
+        uint4 v0 = load_run(0), v1 = load_run(1), v2 = load_run(2), v3 = load_run(3);
+        for (int i = 0; i < n_runs; i += 4) {
+            const uint4 w0 = v0, w1 = v1, w2 = v2, w3 = v3;
+            v0 = load_run(i + 4); v1 = load_run(i + 5); v2 = load_run(i + 6); v3 = load_run(i + 7);
+            process(entries[i], w0);
+            if (i + 1 < n_runs) process(entries[i + 1], w1);
+            if (i + 2 < n_runs) process(entries[i + 2], w2);
+            if (i + 3 < n_runs) process(entries[i + 3], w3);
+        }
     }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) add_run(r, run_sum[r], run_e[r]);
 
     if (a.write_S) {
 #pragma unroll
@@ -207,7 +244,8 @@ hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B,
     a.allow_chain = 1;
     a.da = A.deltas + (size_t)t * pl.tiles_m * pl.s;
     a.db = B.deltas + (size_t)t * pl.tiles_n * pl.s;
-    a.groups = groups;
+    memset(a.first_of_group, 0, sizeof(a.first_of_group));
+    for (int gi = 0; gi < groups.ngroups; ++gi) a.first_of_group[groups.z0[gi]] = 1;
     a.read_S = z0 > 0;
     a.write_S = (z0 + nz) < pl.npairs;
     a.add_to_C = t > 0;
