@@ -8,9 +8,12 @@
 // Eq. 5-6 obtain q through (x + sigma) - sigma with sigma = 0.75 * 2^(rho+c) in FP64: x + sigma lies in the
 // binade whose unit in the last place is 2^(rho+c-53) = 2^(c-b), sigma is an even multiple of that unit,
 // so the FP64 addition rounds x to the nearest multiple of 2^(c-b) with ties to even q, and the
-// subtraction of sigma is exact.  The kernel computes the same q directly on the bit pattern: every
-// element is kept as a signed 64-bit integer `mant` with a fixed power-of-two unit 2^E (x = mant * 2^E),
-// which represents the input and every remainder exactly; no FP64 instruction is executed.
+// subtraction of sigma is exact.  The kernel computes the same q with integers: once an element is within
+// reach of the current unit it is kept as the signed 64-bit fixed-point number x^(p) / 2^(c-b) with 60-b
+// fraction bits, which holds the element and every later remainder exactly (|x^(p)| <= 2^c bounds it by 2^60);
+// q is its rounding to an integer, the remainder is what is left, and moving to the next slice is a left shift
+// by c_p - c_(p+1).  Until then the element is smaller than a quarter of the unit (q = 0) and simply waits with
+// its significand and exponent.  No FP64 instruction is executed.
 //
 // A vector is held in the registers of TPR threads (8*U consecutive elements per thread in U groups of
 // eight) for all s slices, so HBM sees each input element once and each slice code once.
@@ -72,6 +75,7 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
     constexpr int RPB = BLOCK / TPR;                  // vectors per workgroup
     constexpr int EPC = FP16 ? CHUNK_BYTES / 2 : CHUNK_BYTES;   // elements per chunk
     constexpr int WAVES_PER_ROW = TPR / 64;
+    constexpr int ACTIVE = 0x7FFF;
     __shared__ int red[2][BLOCK / 64];
 
     const int tr = threadIdx.x % TPR;
@@ -82,10 +86,17 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
     if (klen > a.kb) klen = a.kb;
     if (row >= a.rows) klen = 0;                      // padding vectors are all zero
     const int64_t padded = a.chunks * EPC;
+    // Fixed-point scale of the working representation: an active element holds T = x^(p) / 2^(c_p - b) * 2^F as a
+    // signed 64-bit integer.  |x^(p)| <= 2^(c_p) bounds |T| by 2^(b+F) = 2^60.
+    const int F = 60 - a.b;
 
-    int64_t mant[8 * U];
-    int ex[8 * U];
+    // Element state.  Dormant (not yet representable exactly with F fraction bits of the current unit): tv = signed
+    // 53-bit significand, pk = (E + F) | (cd << 16) with x = tv * 2^E and cd = ceil(log2 |x|).  Active: tv = T,
+    // pk = ACTIVE.  An element becomes active at the first slice whose unit 2^u satisfies u <= E + F and stays so.
+    int64_t tv[8 * U];
+    int pk[8 * U];
     bool nonfinite = false;
+    int cmax = NO_ELEM;
     const double* src = a.X + row * a.ldv + k0;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -111,23 +122,19 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
             nonfinite |= (e11 == 0x7FF);
             int E = -1074;
             if (e11 != 0) { mm |= 0x0010000000000000ull; E = e11 - 1075; }
-            mant[8 * u + e] = (w >> 63) ? -(int64_t)mm : (int64_t)mm;
-            ex[8 * u + e] = E;
+            const int L = 64 - __clzll((long long)mm);                       // bit length (0 for mm == 0)
+            const int cd = E + L - (((mm & (mm - 1)) == 0) ? 1 : 0);         // smallest c with |x| <= 2^c
+            tv[8 * u + e] = (w >> 63) ? -(int64_t)mm : (int64_t)mm;
+            pk[8 * u + e] = mm == 0 ? ACTIVE : (((E + F) & 0xFFFF) | (cd << 16));
+            cmax = (mm != 0 && cd > cmax) ? cd : cmax;
         }
     }
     if (nonfinite) atomicOr(a.flags, 1);
 
+    int c_prev = 0;
     for (int p = 0; p < a.s; ++p) {
-        // ---- Eq. 4: c = max over the vector of (smallest c_i with |x_i| <= 2^c_i)
-        int cmax = NO_ELEM;
-#pragma unroll
-        for (int i = 0; i < 8 * U; ++i) {
-            const int64_t mv = mant[i];
-            const uint64_t av = (uint64_t)(mv < 0 ? -mv : mv);
-            const int L = 64 - __clzll((long long)av);                 // bit length (0 for av == 0)
-            const int ci = ex[i] + L - (((av & (av - 1)) == 0) ? 1 : 0);  // exact power of two: one less
-            cmax = (av != 0 && ci > cmax) ? ci : cmax;
-        }
+        // ---- Eq. 4: c = max over the vector of ceil(log2 |x_i|); each thread contributes the maximum over its
+        // elements (from the decoded inputs for the first slice, from the remainders afterwards)
 #pragma unroll
         for (int off = 1; off < (TPR < 64 ? TPR : 64); off <<= 1) {
             const int o = __shfl_xor(cmax, off, 64);
@@ -146,33 +153,48 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
         }
         const int c = (cmax == NO_ELEM) ? 0 : cmax;
         const int unit = c - a.b;                                      // the slice's unit is 2^(c-b)
+        // remainders of active elements were left in units of the previous slice: rescale them to this one (a
+        // left shift, exact and inside 2^60 because every remainder is at most 2^c; 0 << anything stays 0)
+        int rescale = p == 0 ? 0 : c_prev - c;
+        rescale = rescale < 0 ? 0 : (rescale > 63 ? 63 : rescale);
+        c_prev = c;
 
         // ---- Eq. 5-8 element by element, eight codes per store
         uint8_t* const dst_slice = a.slices + (size_t)((t * a.s + p) * a.chunks) * (size_t)a.rows_pad * CHUNK_BYTES;
+        uint64_t rmax = 0;                                             // largest |remainder| of this thread's active elements
+        int cdorm = NO_ELEM;                                           // largest cd of its still dormant elements
+        const int64_t round_bias = ((int64_t)1 << (F - 1)) - 1;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             uint32_t codes[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int i = 8 * u + e;
-                const int64_t mv = mant[i];
-                const int sh = unit - ex[i];
+                int64_t T = tv[i];
+                const int st = pk[i];
                 int q = 0;
-                if (mv != 0) {
-                    if (sh <= 0) {                                     // the element is a multiple of the unit
-                        q = (int)(mv << (-sh));
-                        mant[i] = 0;
-                    } else if (sh < 55) {
-                        const uint64_t av = (uint64_t)(mv < 0 ? -mv : mv);
-                        uint64_t qa = av >> sh;
-                        const uint64_t rem = av & ((1ull << sh) - 1);
-                        const uint64_t half = 1ull << (sh - 1);
-                        const uint64_t up = (rem > half) | ((rem == half) & (qa & 1));   // nearest, ties to even
-                        qa += up;
-                        const int64_t r = (int64_t)rem - (int64_t)(up << sh);           // signed remainder
-                        q = (mv < 0) ? -(int)qa : (int)qa;
-                        mant[i] = (mv < 0) ? -r : r;
-                    }                                                  // sh >= 55: |x| < unit/4, q = 0
+                bool active = st == ACTIVE;
+                if (active) {
+                    T <<= rescale;
+                } else {
+                    const int ef = (int)(short)(st & 0xFFFF);
+                    if (unit <= ef) {                                  // representable now: x / 2^unit * 2^F
+                        T <<= (ef - unit);
+                        pk[i] = ACTIVE;
+                        active = true;
+                    } else {
+                        const int cd = st >> 16;
+                        cdorm = cd > cdorm ? cd : cdorm;               // |x| < 2^(unit-3): q = 0, remainder = x
+                    }
+                }
+                if (active) {
+                    // nearest integer to T / 2^F, ties to even (two's complement form), and the exact remainder
+                    const int64_t q64 = (T + round_bias + ((T >> F) & 1)) >> F;
+                    q = (int)q64;
+                    T -= q64 << F;
+                    const uint64_t ar = (uint64_t)(T < 0 ? -T : T);
+                    rmax = ar > rmax ? ar : rmax;
+                    tv[i] = T;
                 }
                 codes[e] = encode_type2<FP16>(q, a.b);
             }
@@ -196,6 +218,13 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
             }
         }
         if (tr == 0) a.exps[(t * a.s + p) * a.rows_pad + row] = c;
+        // this thread's candidate for the next exponent: remainders are rmax * 2^(unit - F)
+        cmax = cdorm;
+        if (rmax != 0) {
+            const int L = 64 - __clzll((long long)rmax);
+            const int ca = unit - F + L - (((rmax & (rmax - 1)) == 0) ? 1 : 0);
+            cmax = ca > cmax ? ca : cmax;
+        }
     }
 }
 
