@@ -54,18 +54,19 @@ struct SplitArgs {
 
 constexpr int NO_ELEM = -(1 << 30);
 
+// Type2 codes of the two values q0 * 2^-b and q1 * 2^-b (|q| <= 2^b), packed low/high.  The hardware FP32 -> FP8
+// (OCP E4M3 on gfx950) and FP32 -> FP16 conversions are exact here because every such value is a normal number of
+// the format; FP32 arithmetic is not FP64 arithmetic, so the integer-only property of the slicer is about FP64.
 template <bool FP16>
-__device__ __forceinline__ uint32_t encode_type2(int q, int b) {
-    // code of the value q * 2^-b, |q| <= 2^b; every such value is a normal number of the format
-    if (q == 0) return 0;
-    uint32_t a = (uint32_t)(q < 0 ? -q : q);
-    int L = 32 - __clz((int)a);                       // 2^(L-1) <= a < 2^L
+__device__ __forceinline__ uint32_t encode_type2_pair(int q0, int q1, int b) {
+    const float f0 = ldexpf((float)q0, -b), f1 = ldexpf((float)q1, -b);
     if (FP16) {
-        uint32_t frac = ((a << 11) >> L) & 0x3FFu;    // the 10 bits below the leading one
-        return ((q < 0) ? 0x8000u : 0u) | ((uint32_t)(L - 1 - b + 15) << 10) | frac;
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        const h2 h = {(_Float16)f0, (_Float16)f1};
+        return __builtin_bit_cast(uint32_t, h);                       // q = 0 gives +0.0, code 0
     } else {
-        uint32_t frac = ((a << 4) >> L) & 0x7u;       // the 3 bits below the leading one (a <= 16)
-        return ((q < 0) ? 0x80u : 0u) | ((uint32_t)(L - 1 - b + 7) << 3) | frac;
+        const uint32_t w = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(f0, f1, 0, false) & 0xFFFFu;
+        return w;
     }
 }
 
@@ -166,7 +167,7 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
         const int64_t round_bias = ((int64_t)1 << (F - 1)) - 1;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            uint32_t codes[8];
+            int qs[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int i = 8 * u + e;
@@ -196,23 +197,26 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
                     rmax = ar > rmax ? ar : rmax;
                     tv[i] = T;
                 }
-                codes[e] = encode_type2<FP16>(q, a.b);
+                qs[e] = q;
             }
+            uint32_t c2[4];                                            // two codes each
+#pragma unroll
+            for (int e = 0; e < 4; ++e) c2[e] = encode_type2_pair<FP16>(qs[2 * e], qs[2 * e + 1], a.b);
             const int64_t ke = 8 * ((int64_t)tr + (int64_t)TPR * u);
             if (ke < padded) {
                 const int64_t kc = ke / EPC;
                 uint8_t* dst = dst_slice + ((size_t)kc * a.rows_pad + row) * CHUNK_BYTES + (ke % EPC) * (FP16 ? 2 : 1);
                 if (FP16) {
                     uint4 w;
-                    w.x = codes[0] | (codes[1] << 16);
-                    w.y = codes[2] | (codes[3] << 16);
-                    w.z = codes[4] | (codes[5] << 16);
-                    w.w = codes[6] | (codes[7] << 16);
+                    w.x = c2[0];
+                    w.y = c2[1];
+                    w.z = c2[2];
+                    w.w = c2[3];
                     *reinterpret_cast<uint4*>(dst) = w;
                 } else {
                     uint2 w;
-                    w.x = codes[0] | (codes[1] << 8) | (codes[2] << 16) | (codes[3] << 24);
-                    w.y = codes[4] | (codes[5] << 8) | (codes[6] << 16) | (codes[7] << 24);
+                    w.x = c2[0] | (c2[1] << 16);
+                    w.y = c2[2] | (c2[3] << 16);
                     *reinterpret_cast<uint2*>(dst) = w;
                 }
             }
