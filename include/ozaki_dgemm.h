@@ -53,6 +53,10 @@ enum {
     OZAKI_STATUS_NONFINITE = 5     /* reported by ozaki_last_device_status: A or B held an Inf or NaN      */
 };
 
+/* OR-ed into a num_slices argument: multiply all s*s slice pairs (the setting of the paper's Table 2 and
+ * Section 5.3) instead of only the s(s+1)/2 pairs with p + q <= s + 1. */
+#define OZAKI_PAIRS_ALL 0x100
+
 #define OZAKI_MAX_SLICES 32
 #define OZAKI_MAX_K_BLOCK 32768
 
@@ -81,7 +85,8 @@ int ozaki_plan(int64_t k_block, int slice_format, int* rho_out, int* bits_out);
  *                 accumulated anti-diagonal by anti-diagonal, least significant first; products of one
  *                 anti-diagonal that carry the same power-of-two scale for an element are summed exactly
  *                 before the (rounded) FP64 addition.
- *                 0 selects a data-independent default (ceil(61 / (b+1)) slices).
+ *                 0 selects a data-independent default (ceil(61 / (b+1)) slices).  OR-ing OZAKI_PAIRS_ALL
+ *                 into the value multiplies all s*s pairs (anti-diagonals 2s ... 2, same accumulation rule).
  *   k_block       inner-product-wise block length (Section 4.3); 0 means k (no blocking).  A last,
  *                 shorter block is allowed.  Must not exceed OZAKI_MAX_K_BLOCK elements.
  *   accum_mode    OZAKI_ACCUM_*

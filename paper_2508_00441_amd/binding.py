@@ -19,6 +19,7 @@ SLICE_FP16 = 1
 ACCUM_FP64_HW = 0
 ACCUM_FP64_INT_EMU = 1
 STATUS_OK, STATUS_INFEASIBLE, STATUS_WORKSPACE, STATUS_HIP_ERROR, STATUS_NONFINITE = 0, 1, 3, 4, 5
+PAIRS_ALL = 0x100
 MAX_SLICES = 32
 MAX_K_BLOCK = 32768
 

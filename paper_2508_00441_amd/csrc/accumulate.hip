@@ -41,14 +41,13 @@ struct AccArgs {
     int64_t rows_pad_a, rows_pad_b;
     int64_t m, n;
     int tiles_m, tiles_n;
-    int z0, nz, s;
     int two_b;               // 2b: the products are integer multiples of 2^-two_b
     int read_S, write_S, add_to_C;
     int allow_chain;
     const int32_t* da;       // deltas of the block: [tiles_m][s]
     const int32_t* db;       // [tiles_n][s]
-    PairList pairs;
-    uint8_t first_of_group[MAX_PAIRS];   // per pair of the list: 1 if it opens a group
+    PairOrder order;
+    Pass pass;
 };
 
 template <bool EMU>
@@ -69,7 +68,7 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
     const int64_t n0 = (int64_t)tn * TILE + wn * 128 + ti * 32;       // first column
 
     // exponents of the 32 rows and 32 columns: slot 0 keeps the first-slice exponent, slots p >= 1 the difference to it
-    for (int idx = tid; idx < a.s * 32; idx += 256) {
+    for (int idx = tid; idx < a.order.s * 32; idx += 256) {
         const int p = idx >> 5, r = idx & 31;
         const int ca = a.ea[(int64_t)p * a.rows_pad_a + m0 + r], ca1 = a.ea[m0 + r];
         const int cb = a.eb[(int64_t)p * a.rows_pad_b + n0 + r], cb1 = a.eb[n0 + r];
@@ -94,25 +93,26 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
     }
 
     // The stored runs of this tile, in accumulation order: a pair starts a run unless it is linked (for the whole
-    // tile) to the pair before it inside its group.  Built by the first wave, 64 pairs at a time.
+    // tile) to the pair before it inside its group.  Built by the first wave, one anti-diagonal at a time (an
+    // anti-diagonal has at most 32 pairs).
     if (tid < 64) {
-        const int32_t* dA = a.da + (size_t)tm * a.s;
-        const int32_t* dB = a.db + (size_t)tn * a.s;
-        int count = 0;
-        for (int base = 0; base < a.nz; base += 64) {
-            const int zl = base + tid;
+        const int32_t* dA = a.da + (size_t)tm * a.order.s;
+        const int32_t* dB = a.db + (size_t)tn * a.order.s;
+        int count = 0, slot0 = 0;
+        for (int g = a.pass.g_hi; g >= a.pass.g_lo; --g) {
+            const int len = diag_len(a.order, g);
             bool start = false;
             uint32_t entry = 0;
-            if (zl < a.nz) {
-                const int z = a.z0 + zl;
-                const int p = a.pairs.p[z] - 1, q = a.pairs.q[z] - 1;
-                const bool first = a.first_of_group[z] != 0;
+            if (tid < len) {
+                const int p = diag_first_p(a.order, g) + tid - 1, q = g - p - 2;     // 0-based slice indices
+                const bool first = tid % a.order.run_limit == 0;
                 start = first || !(a.allow_chain && pair_linked(dA, dB, p - 1, q + 1));
-                entry = (uint32_t)zl | ((uint32_t)p << 12) | ((uint32_t)q << 18) | ((uint32_t)first << 24);
+                entry = (uint32_t)(slot0 + tid) | ((uint32_t)p << 12) | ((uint32_t)q << 18) | ((uint32_t)first << 24);
             }
             const unsigned long long mask = __ballot(start);
             if (start) entries[count + __popcll(mask & ((1ull << tid) - 1ull))] = entry;
             count += __popcll(mask);
+            slot0 += len;
         }
         if (tid == 0) n_entries = count;
     }
@@ -229,8 +229,8 @@ unsigned grid_for(int64_t work_items) {
 
 }  // namespace
 
-hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B, const PairList& pairs,
-                             const GroupList& groups, int64_t t, int z0, int nz, const float* P, double* S_io,
+hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B, const PairOrder& order, const Pass& ps,
+                             bool first_pass, bool last_pass, int64_t t, const float* P, double* S_io,
                              double* C, int64_t ldc, int accum_mode, hipStream_t st) {
     if (pl.tiles_m == 0 || pl.tiles_n == 0) return hipSuccess;
     AccArgs a;
@@ -239,17 +239,14 @@ hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B,
     a.eb = B.exps + (size_t)t * pl.s * B.rows_pad;
     a.rows_pad_a = A.rows_pad; a.rows_pad_b = B.rows_pad;
     a.m = pl.m; a.n = pl.n; a.tiles_m = (int)pl.tiles_m; a.tiles_n = (int)pl.tiles_n;
-    a.z0 = z0; a.nz = nz; a.s = pl.s;
     a.two_b = 2 * pl.b;
     a.allow_chain = 1;
     a.da = A.deltas + (size_t)t * pl.tiles_m * pl.s;
     a.db = B.deltas + (size_t)t * pl.tiles_n * pl.s;
-    memset(a.first_of_group, 0, sizeof(a.first_of_group));
-    for (int gi = 0; gi < groups.ngroups; ++gi) a.first_of_group[groups.z0[gi]] = 1;
-    a.read_S = z0 > 0;
-    a.write_S = (z0 + nz) < pl.npairs;
+    a.order = order; a.pass = ps;
+    a.read_S = !first_pass;
+    a.write_S = !last_pass;
     a.add_to_C = t > 0;
-    a.pairs = pairs;
     const int64_t blocks = pl.tiles_m * pl.tiles_n * 64;
     if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
     if (accum_mode == 1) hipLaunchKernelGGL((accumulate_kernel<true>), dim3((unsigned)blocks), dim3(256), 0, st, a);

@@ -46,12 +46,12 @@ int slice_bits(int64_t kb, int fmt) {
 }
 
 // Builds the plan; returns 0 or a status / negative argument index in the numbering of ozaki_dgemm.
-int make_plan(int64_t m, int64_t n, int64_t k, int fmt, int s, int64_t k_block, Plan& pl) {
+int make_plan(int64_t m, int64_t n, int64_t k, int fmt, int s, int64_t k_block, bool full, Plan& pl) {
     if (m < 0) return -1;
     if (n < 0) return -2;
     if (k < 0) return -3;
     if (fmt != OZAKI_SLICE_FP8_E4M3 && fmt != OZAKI_SLICE_FP16) return -10;
-    if (s < 0) return -11;
+    if (s < 0 || s > 0xFF) return -11;
     if (k_block < 0) return -12;
     memset(&pl, 0, sizeof(pl));
     pl.m = m; pl.n = n; pl.k = k; pl.fmt = fmt; pl.elem_bytes = fmt == OZAKI_SLICE_FP16 ? 2 : 1;
@@ -66,7 +66,8 @@ int make_plan(int64_t m, int64_t n, int64_t k, int fmt, int s, int64_t k_block, 
     pl.T = k == 0 ? 0 : (k + pl.kb - 1) / pl.kb;
     const int64_t epc = CHUNK_BYTES / pl.elem_bytes;
     pl.chunks = (pl.kb + epc - 1) / epc;
-    pl.npairs = pl.s * (pl.s + 1) / 2;
+    pl.full = full ? 1 : 0;
+    pl.npairs = full ? pl.s * pl.s : pl.s * (pl.s + 1) / 2;
     pl.run_limit = (int)(((int64_t)1 << 24) / (pl.kb << (2 * pl.b)));
     if (pl.run_limit < 1) pl.run_limit = 1;
     pl.tiles_m = (m + TILE - 1) / TILE;
@@ -74,31 +75,6 @@ int make_plan(int64_t m, int64_t n, int64_t k, int fmt, int s, int64_t k_block, 
     pl.m_pad = pl.tiles_m * TILE;
     pl.n_pad = pl.tiles_n * TILE;
     return 0;
-}
-
-void make_pairs(int s, PairList& pr) {
-    int z = 0;
-    for (int gsum = s + 1; gsum >= 2; --gsum)
-        for (int p = 1; p < gsum; ++p) {
-            const int q = gsum - p;
-            if (p <= s && q <= s) { pr.p[z] = (uint8_t)p; pr.q[z] = (uint8_t)q; ++z; }
-        }
-}
-
-// Groups of the pairs [z0, z1): every anti-diagonal is cut into runs of at most run_limit consecutive pairs.
-// [z0, z1) must consist of whole anti-diagonals.
-void make_groups(const Plan& pl, const PairList& pr, int z0, int z1, GroupList& gl) {
-    gl.ngroups = 0;
-    int z = z0;
-    while (z < z1) {
-        const int diag = pr.p[z] + pr.q[z];
-        int len = 1;
-        while (z + len < z1 && len < pl.run_limit && len < 255 && pr.p[z + len] + pr.q[z + len] == diag) ++len;
-        gl.z0[gl.ngroups] = (uint16_t)z;
-        gl.len[gl.ngroups] = (uint8_t)len;
-        ++gl.ngroups;
-        z += len;
-    }
 }
 
 struct Carve {
@@ -168,19 +144,20 @@ bool carve(const Plan& pl, Carve& c) {
     return c.chunk_pairs >= pl.s;
 }
 
-// End (exclusive) of the pass that starts at pair z0: as many whole anti-diagonals as fit into `capacity`
-// products.  Anti-diagonal g = s+1 ... 2 has g-1 pairs and the list starts with g = s+1.
-int pass_end(const Plan& pl, int z0, int capacity) {
-    int z = 0, end = z0;
-    for (int gsum = pl.s + 1; gsum >= 2; --gsum) {
-        const int len = gsum - 1;
-        if (z >= z0) {
-            if (z + len - z0 > capacity) break;
-            end = z + len;
-        }
-        z += len;
+PairOrder order_of(const Plan& pl) { return PairOrder{pl.s, pl.full, pl.run_limit}; }
+
+// The pass that starts at anti-diagonal g_hi: as many whole anti-diagonals as fit into `capacity` products (at
+// least one: the carve-up guarantees room for the longest anti-diagonal).
+Pass next_pass(const PairOrder& o, int g_hi, int capacity) {
+    Pass ps{g_hi, g_hi, 0, 0};
+    for (int g = g_hi; g >= 2; --g) {
+        const int len = diag_len(o, g);
+        if (ps.npairs > 0 && ps.npairs + len > capacity) break;
+        ps.g_lo = g;
+        ps.npairs += len;
+        ps.ngroups += diag_groups(o, g);
     }
-    return end;
+    return ps;
 }
 
 // ---- profiling spans -------------------------------------------------------------------------------------------
@@ -240,13 +217,13 @@ int ozaki_set_stream(void* hip_stream) {
 
 size_t ozaki_workspace_bytes(int64_t m, int64_t n, int64_t k, int slice_format, int num_slices, int64_t k_block) {
     Plan pl;
-    if (make_plan(m, n, k, slice_format, num_slices, k_block, pl) != 0) return 0;
+    if (make_plan(m, n, k, slice_format, num_slices & ~OZAKI_PAIRS_ALL, k_block, (num_slices & OZAKI_PAIRS_ALL) != 0, pl) != 0) return 0;
     return recommended_bytes(pl);
 }
 
 size_t ozaki_workspace_min_bytes(int64_t m, int64_t n, int64_t k, int slice_format, int num_slices, int64_t k_block) {
     Plan pl;
-    if (make_plan(m, n, k, slice_format, num_slices, k_block, pl) != 0) return 0;
+    if (make_plan(m, n, k, slice_format, num_slices & ~OZAKI_PAIRS_ALL, k_block, (num_slices & OZAKI_PAIRS_ALL) != 0, pl) != 0) return 0;
     return minimum_bytes(pl);
 }
 
@@ -309,7 +286,7 @@ int ozaki_profile_read(float* ms_out, int* launches_out) {
 int ozaki_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb,
                 double* C, int64_t ldc, int slice_format, int num_slices, int64_t k_block, int accum_mode) {
     Plan pl;
-    const int st = make_plan(m, n, k, slice_format, num_slices, k_block, pl);
+    const int st = make_plan(m, n, k, slice_format, num_slices & ~OZAKI_PAIRS_ALL, k_block, (num_slices & OZAKI_PAIRS_ALL) != 0, pl);
     if (st != 0) return st;
     if (accum_mode != OZAKI_ACCUM_FP64_HW && accum_mode != OZAKI_ACCUM_FP64_INT_EMU) return -13;
     if (m == 0 || n == 0) return 0;
@@ -325,25 +302,23 @@ int ozaki_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, c
     if (ldb < (k > 1 ? k : 1)) return -7;
     Carve c;
     if (!carve(pl, c)) return OZAKI_STATUS_WORKSPACE;
-    PairList pairs;
-    make_pairs(pl.s, pairs);
+    const PairOrder order = order_of(pl);
 
     int rc = run_split(pl, c, A, lda, B, ldb, true, true);
     if (rc) return rc;
     for (int64_t t = 0; t < pl.T; ++t) {
-        for (int z0 = 0; z0 < pl.npairs;) {
-            const int nz = pass_end(pl, z0, c.chunk_pairs) - z0;
-            GroupList groups;
-            make_groups(pl, pairs, z0, z0 + nz, groups);
+        for (int g_hi = order_top_diag(order); g_hi >= 2;) {
+            const Pass ps = next_pass(order, g_hi, c.chunk_pairs);
             {
                 Phase ph(1);
-                HIP_TRY(launch_pair_gemm(pl, c.A, c.B, pairs, groups, true, t, z0, nz, c.P, g.stream));
+                HIP_TRY(launch_pair_gemm(pl, c.A, c.B, order, ps, true, t, c.P, g.stream));
             }
             {
                 Phase ph(2);
-                HIP_TRY(launch_accumulate(pl, c.A, c.B, pairs, groups, t, z0, nz, c.P, c.S, C, ldc, accum_mode, g.stream));
+                HIP_TRY(launch_accumulate(pl, c.A, c.B, order, ps, g_hi == order_top_diag(order), ps.g_lo == 2, t, c.P, c.S, C, ldc,
+                                          accum_mode, g.stream));
             }
-            z0 += nz;
+            g_hi = ps.g_lo - 1;
         }
     }
     return 0;
@@ -357,7 +332,7 @@ int ozaki_split(int is_B, int64_t rows, int64_t k, const double* X, int64_t ldx,
     if (num_slices < 1) return -7;
     Plan pl;
     // plan with the operand in the role it has in the product; the other dimension is irrelevant here
-    const int st = make_plan(is_B ? 0 : rows, is_B ? rows : 0, k, slice_format, num_slices, k_block, pl);
+    const int st = make_plan(is_B ? 0 : rows, is_B ? rows : 0, k, slice_format, num_slices, k_block, false, pl);
     if (st < 0) return st == -10 ? -6 : st == -12 ? -8 : st;
     if (st != 0) return st;
     if (rows == 0 || k == 0) return 0;
@@ -380,7 +355,7 @@ int ozaki_split(int is_B, int64_t rows, int64_t k, const double* X, int64_t ldx,
 int ozaki_pair_products(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb,
                         int slice_format, int num_slices, int64_t k_block, float* P_out) {
     Plan pl;
-    int st = make_plan(m, n, k, slice_format, num_slices, k_block, pl);
+    int st = make_plan(m, n, k, slice_format, num_slices & ~OZAKI_PAIRS_ALL, k_block, (num_slices & OZAKI_PAIRS_ALL) != 0, pl);
     if (st < 0) return st == -10 ? -8 : st == -11 ? -9 : st == -12 ? -10 : st;
     if (st != 0) return st;
     if (num_slices < 1) return -9;
@@ -392,19 +367,19 @@ int ozaki_pair_products(int64_t m, int64_t n, int64_t k, const double* A, int64_
     if (!P_out) return -11;
     Carve c;
     if (!carve(pl, c)) return OZAKI_STATUS_WORKSPACE;
-    PairList pairs;
-    make_pairs(pl.s, pairs);
+    const PairOrder order = order_of(pl);
     int rc = run_split(pl, c, A, lda, B, ldb, true, true);
     if (rc) return rc;
-    for (int64_t t = 0; t < pl.T; ++t)
-        for (int z0 = 0; z0 < pl.npairs;) {
-            const int nz = pass_end(pl, z0, c.chunk_pairs) - z0;
-            GroupList groups;
-            make_groups(pl, pairs, z0, z0 + nz, groups);
-            HIP_TRY(launch_pair_gemm(pl, c.A, c.B, pairs, groups, false, t, z0, nz, c.P, g.stream));
-            HIP_TRY(launch_export_products(pl, nz, c.P, P_out + ((size_t)t * pl.npairs + z0) * (size_t)m * n, g.stream));
-            z0 += nz;
+    for (int64_t t = 0; t < pl.T; ++t) {
+        int z0 = 0;
+        for (int g_hi = order_top_diag(order); g_hi >= 2;) {
+            const Pass ps = next_pass(order, g_hi, c.chunk_pairs);
+            HIP_TRY(launch_pair_gemm(pl, c.A, c.B, order, ps, false, t, c.P, g.stream));
+            HIP_TRY(launch_export_products(pl, ps.npairs, c.P, P_out + ((size_t)t * pl.npairs + z0) * (size_t)m * n, g.stream));
+            z0 += ps.npairs;
+            g_hi = ps.g_lo - 1;
         }
+    }
     return 0;
 }
 

@@ -7,7 +7,7 @@
 namespace ozaki {
 
 constexpr int MAX_SLICES = 32;
-constexpr int MAX_PAIRS = MAX_SLICES * (MAX_SLICES + 1) / 2;
+constexpr int MAX_PAIRS = MAX_SLICES * MAX_SLICES;      // all s*s pairs in the full mode
 constexpr int64_t MAX_K_BLOCK = 32768;
 
 // ---- tiling of the slice-pair GEMM: one workgroup computes one TILE x TILE block of one pair product ------
@@ -41,25 +41,61 @@ struct Plan {
     int64_t kb;           // block length (elements)
     int64_t T;            // number of blocks
     int64_t chunks;       // chunks per block
-    int npairs;           // s(s+1)/2
+    int full;             // 1: all s*s pairs, 0: the pairs with p + q <= s + 1
+    int npairs;           // s(s+1)/2 or s*s
     int run_limit;        // floor(2^24 / (kb * 4^b)): equal-scale pair products that may be summed exactly in FP32
     int64_t tiles_m, tiles_n;
     int64_t m_pad, n_pad;
 };
 
-// Slice pairs in accumulation order (least significant anti-diagonal first), 1-based slice indices.
-struct PairList {
-    uint8_t p[MAX_PAIRS];
-    uint8_t q[MAX_PAIRS];
+// The slice pairs (p, q), 1-based, and their accumulation order: anti-diagonals g = p + q from the least
+// significant (largest g) down to g = 2, p ascending inside one.  Triangle mode uses the pairs with p + q <= s + 1,
+// full mode all s * s.  Every anti-diagonal is cut into groups of at most run_limit consecutive pairs (the unit
+// whose equal-scale products are summed exactly before the FP64 addition); pairs are numbered z = 0, 1, ... in this
+// order.  Everything below is a closed form of (s, full, run_limit), evaluated on the host and in the kernels.
+struct PairOrder {
+    int s;
+    int full;
+    int run_limit;
+};
+__host__ __device__ inline int order_top_diag(const PairOrder& o) { return o.full ? 2 * o.s : o.s + 1; }
+__host__ __device__ inline int diag_first_p(const PairOrder& o, int g) { return g - o.s > 1 ? g - o.s : 1; }
+__host__ __device__ inline int diag_len(const PairOrder& o, int g) {
+    const int hi = g - 1 < o.s ? g - 1 : o.s;
+    return hi - diag_first_p(o, g) + 1;
+}
+__host__ __device__ inline int diag_groups(const PairOrder& o, int g) { return (diag_len(o, g) + o.run_limit - 1) / o.run_limit; }
+__host__ __device__ inline int order_num_pairs(const PairOrder& o) { return o.full ? o.s * o.s : o.s * (o.s + 1) / 2; }
+
+// A pass of the accumulation: the anti-diagonals g_hi, g_hi - 1, ..., g_lo; its pair products occupy the slots
+// 0 .. npairs-1 of the product buffer in pair order.
+struct Pass {
+    int g_hi, g_lo;
+    int npairs, ngroups;
 };
 
-// Consecutive pairs of one anti-diagonal, at most Plan::run_limit of them, never crossing a multiple of run_limit
-// inside the anti-diagonal: the unit whose equal-scale products are summed exactly before the FP64 addition.
-struct GroupList {
-    int ngroups;
-    uint16_t z0[MAX_PAIRS];   // index of the group's first pair in the PairList
-    uint8_t len[MAX_PAIRS];
+// The gi-th group of a pass: slices (p0 + j, q0 - j), j < len (1-based), first product slot `slot`.
+struct Group {
+    int p0, q0, len, slot;
 };
+__host__ __device__ inline Group pass_group(const PairOrder& o, const Pass& ps, int gi) {
+    int slot = 0;
+    for (int g = ps.g_hi; g >= ps.g_lo; --g) {
+        const int len = diag_len(o, g), ng = (len + o.run_limit - 1) / o.run_limit;
+        if (gi < ng) {
+            const int pos = gi * o.run_limit;
+            Group r;
+            r.p0 = diag_first_p(o, g) + pos;
+            r.q0 = g - r.p0;
+            r.len = len - pos < o.run_limit ? len - pos : o.run_limit;
+            r.slot = slot + pos;
+            return r;
+        }
+        gi -= ng;
+        slot += len;
+    }
+    return Group{1, 1, 0, 0};
+}
 
 // True if, for every element of the tile, pair (p+1, q-1) carries the same scale factor 2^(cA + cB) as pair
 // (p, q) (0-based slice indices): then the two products can be summed in the FP32 accumulator of the matrix unit
@@ -97,18 +133,17 @@ hipError_t launch_export_slices(const Plan& pl, const Operand& op, void* out, hi
 // Fills Operand::deltas from Operand::exps.
 hipError_t launch_deltas(const Plan& pl, const Operand& op, hipStream_t st);
 
-// Products of the pairs of `groups` (all inside [z0, z0+nz)) of block t into P ([nz][tiles_n][tiles_m][TILE_ELEMS]
-// floats, slot = pair index - z0).  With allow_chain, consecutive pairs of a group that are linked for a tile
-// (pair_linked) form a run whose exact sum is stored in the slot of the run's first pair; the slots of the
-// other pairs of the run are left untouched.
-hipError_t launch_pair_gemm(const Plan& pl, const Operand& A, const Operand& B, const PairList& pairs,
-                            const GroupList& groups, bool allow_chain, int64_t t, int z0, int nz, float* P, hipStream_t st);
+// Products of the pairs of pass `ps` of block t into P ([ps.npairs][tiles_n][tiles_m][TILE_ELEMS] floats).  With
+// allow_chain, consecutive pairs of a group that are linked for a tile (pair_linked) form a run whose exact sum is
+// stored in the slot of the run's first pair; the slots of the other pairs of the run are left untouched.
+hipError_t launch_pair_gemm(const Plan& pl, const Operand& A, const Operand& B, const PairOrder& order, const Pass& ps,
+                            bool allow_chain, int64_t t, float* P, hipStream_t st);
 
-// Accumulate pairs [z0, z0+nz) of block t.  S_io: running block sum in accumulator order (read when z0 > 0,
-// written unless the chunk is the block's last one).  On the last chunk the block sum is rescaled by the
+// Accumulate the pairs of pass `ps` of block t.  S_io: running block sum in accumulator order (read unless the
+// pass is the block's first, written unless it is the last).  On the last pass the block sum is rescaled by the
 // first-slice exponents and stored to C (t == 0) or added to C (t > 0).
-hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B, const PairList& pairs,
-                             const GroupList& groups, int64_t t, int z0, int nz, const float* P, double* S_io,
+hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B, const PairOrder& order, const Pass& ps,
+                             bool first_pass, bool last_pass, int64_t t, const float* P, double* S_io,
                              double* C, int64_t ldc, int accum_mode, hipStream_t st);
 
 // P in accumulator order -> [nz][n][m] column-major matrices (verification export).

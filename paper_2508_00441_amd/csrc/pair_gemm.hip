@@ -48,13 +48,11 @@ struct GemmArgs {
     int64_t rows_pad_a, rows_pad_b;
     int64_t chunks;
     int tiles_m, tiles_n;
-    int z0;                  // first pair of this launch: P slot = pair index - z0
-    int s;
     int allow_chain;
     const int32_t* da;       // A deltas of the block: [tiles_m][s]
     const int32_t* db;       // B deltas of the block: [tiles_n][s]
-    PairList pairs;
-    GroupList groups;
+    PairOrder order;
+    Pass pass;
 };
 
 constexpr int BK = CHUNK_BYTES;                       // bytes of the inner dimension per row and stage
@@ -94,16 +92,16 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
     const int gi = blockIdx.x / tiles;
     const int tile = blockIdx.x - gi * tiles;
     const int tn = tile / a.tiles_m, tm = tile - tn * a.tiles_m;
-    const int gz = a.groups.z0[gi], glen = a.groups.len[gi];
-    const int p0 = a.pairs.p[gz] - 1, q0 = a.pairs.q[gz] - 1;
+    const Group grp = pass_group(a.order, a.pass, gi);
+    const int glen = grp.len, p0 = grp.p0 - 1, q0 = grp.q0 - 1;       // 0-based slice indices from here on
     const int chunks = (int)a.chunks;
     // bit j of `links`: pair j+1 of the group carries, for every element of this tile, the same scale factor as
     // pair j, so its product keeps accumulating on top of pair j's (the sum stays inside the exact FP32 window
     // because a group has at most run_limit pairs); otherwise the accumulators are stored and cleared in between
     unsigned links = 0;
     if (a.allow_chain) {
-        const int32_t* dA = a.da + (size_t)tm * a.s;
-        const int32_t* dB = a.db + (size_t)tn * a.s;
+        const int32_t* dA = a.da + (size_t)tm * a.order.s;
+        const int32_t* dB = a.db + (size_t)tn * a.order.s;
         for (int j = 0; j + 1 < glen; ++j) links |= pair_linked(dA, dB, p0 + j, q0 - j) ? (1u << j) : 0u;
     }
 
@@ -273,7 +271,7 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
         // the run's first pair and clear them (the stores only make the next vmcnt wait stricter).
         const bool last_pair = jp + 1 == glen;
         if (last_pair || !((links >> jp) & 1u)) {
-            store_acc(gz + run_start - a.z0);
+            store_acc(grp.slot + run_start);
             if (!last_pair) zero_acc();
             run_start = jp + 1;
         }
@@ -288,20 +286,21 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
 
 }  // namespace
 
-hipError_t launch_pair_gemm(const Plan& pl, const Operand& A, const Operand& B, const PairList& pairs,
-                            const GroupList& groups, bool allow_chain, int64_t t, int z0, int nz, float* P, hipStream_t st) {
-    if (nz <= 0 || groups.ngroups <= 0 || pl.tiles_m == 0 || pl.tiles_n == 0 || pl.chunks == 0) return hipSuccess;
+hipError_t launch_pair_gemm(const Plan& pl, const Operand& A, const Operand& B, const PairOrder& order, const Pass& ps,
+                            bool allow_chain, int64_t t, float* P, hipStream_t st) {
+    if (ps.ngroups <= 0 || pl.tiles_m == 0 || pl.tiles_n == 0 || pl.chunks == 0) return hipSuccess;
     GemmArgs a;
     const size_t slice_a = (size_t)pl.chunks * A.rows_pad * CHUNK_BYTES, slice_b = (size_t)pl.chunks * B.rows_pad * CHUNK_BYTES;
     a.sa = A.slices + (size_t)t * pl.s * slice_a;
     a.sb = B.slices + (size_t)t * pl.s * slice_b;
     a.P = P;
     a.rows_pad_a = A.rows_pad; a.rows_pad_b = B.rows_pad; a.chunks = pl.chunks;
-    a.tiles_m = (int)pl.tiles_m; a.tiles_n = (int)pl.tiles_n; a.z0 = z0; a.pairs = pairs; a.groups = groups;
-    a.s = pl.s; a.allow_chain = allow_chain ? 1 : 0;
+    a.tiles_m = (int)pl.tiles_m; a.tiles_n = (int)pl.tiles_n;
+    a.allow_chain = allow_chain ? 1 : 0;
     a.da = A.deltas + (size_t)t * pl.tiles_m * pl.s;
     a.db = B.deltas + (size_t)t * pl.tiles_n * pl.s;
-    const int64_t blocks = (int64_t)groups.ngroups * pl.tiles_m * pl.tiles_n;
+    a.order = order; a.pass = ps;
+    const int64_t blocks = (int64_t)ps.ngroups * pl.tiles_m * pl.tiles_n;
     if (blocks > 0x7FFFFFFF || pl.chunks > 0x7FFFFFFF) return hipErrorInvalidValue;
     if (pl.fmt == 1) hipLaunchKernelGGL((pair_gemm_kernel<true>), dim3((unsigned)blocks), dim3(256), 0, st, a);
     else hipLaunchKernelGGL((pair_gemm_kernel<false>), dim3((unsigned)blocks), dim3(256), 0, st, a);

@@ -12,8 +12,9 @@
 // reach of the current unit it is kept as the signed 64-bit fixed-point number x^(p) / 2^(c-b) with 60-b
 // fraction bits, which holds the element and every later remainder exactly (|x^(p)| <= 2^c bounds it by 2^60);
 // q is its rounding to an integer, the remainder is what is left, and moving to the next slice is a left shift
-// by c_p - c_(p+1).  Until then the element is smaller than a quarter of the unit (q = 0) and simply waits with
-// its significand and exponent.  No FP64 instruction is executed.
+// by c_p - c_(p+1).  Until then the element waits with its significand and exponent: with b <= 7 it is then smaller
+// than half the unit (q = 0); with wider slices it can already reach the unit, and is rounded in its integer form.
+// No FP64 instruction is executed.
 //
 // A vector is held in the registers of TPR threads (8*U consecutive elements per thread in U groups of
 // eight) for all s slices, so HBM sees each input element once and each slice code once.
@@ -183,9 +184,27 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
                         T <<= (ef - unit);
                         pk[i] = ACTIVE;
                         active = true;
+                    } else if (unit - ef + F <= 53) {
+                        // Wide slices only (b >= 8, fewer than 53 fraction bits): the element reaches the unit but its
+                        // low bits do not fit the fixed-point form yet.  Round its integer form tv * 2^E directly, by
+                        // sh = unit - E bits, and let the remainder wait on as a dormant element with the same E.
+                        const int sh = unit - ef + F;                  // F < sh <= 53
+                        const int64_t q64 = (T + (((int64_t)1 << (sh - 1)) - 1) + ((T >> sh) & 1)) >> sh;
+                        q = (int)q64;
+                        T -= q64 << sh;
+                        tv[i] = T;
+                        const uint64_t ar = (uint64_t)(T < 0 ? -T : T);
+                        if (ar == 0) {
+                            pk[i] = ACTIVE;                            // nothing left: an active zero
+                        } else {
+                            const int L = 64 - __clzll((long long)ar);
+                            const int cd = ef - F + L - (((ar & (ar - 1)) == 0) ? 1 : 0);
+                            pk[i] = (st & 0xFFFF) | (cd << 16);
+                            cdorm = cd > cdorm ? cd : cdorm;
+                        }
                     } else {
                         const int cd = st >> 16;
-                        cdorm = cd > cdorm ? cd : cdorm;               // |x| < 2^(unit-3): q = 0, remainder = x
+                        cdorm = cd > cdorm ? cd : cdorm;               // |x| < 2^(unit-1): q = 0, remainder = x
                     }
                 }
                 if (active) {

@@ -72,6 +72,10 @@ SPLIT_CASES = [
     ("fp8", 9, 20000, 0, 5, 1.0),         # 1024-thread configuration
     ("fp16", 33, 16384, 4096, 9, 1.0),
     ("fp8", 17, 3, 0, 4, 1.0),            # tiny k
+    ("fp16", 40, 200, 0, 6, 1.0),         # b = 8
+    ("fp16", 40, 64, 0, 5, 2.0),          # b = 9
+    ("fp16", 33, 16, 0, 5, 1.0),          # b = 10
+    ("fp16", 19, 700, 256, 5, 2.0),       # b = 8, three blocks
 ]
 
 
@@ -161,6 +165,34 @@ def test_dgemm_matches_oracle(fmt, m, n, k, k_block, s, phi, accum):
     e_ab, e_c, _, _ = exact.sampled_errors(A, B, ent, [C[i, j] for i, j in ent])
     if s >= 7:
         assert e_ab <= 4 * k * 2.0 ** -53
+    ws.close()
+
+
+@pytest.mark.parametrize("fmt,m,n,k,k_block,s,phi", [("fp8", 300, 270, 520, 0, 7, 1.0), ("fp16", 130, 260, 700, 256, 5, 2.0),
+                                                     ("fp8", 64, 64, 4096, 0, 11, 0.5)])
+@pytest.mark.parametrize("accum", ["hw", "emu"])
+def test_all_pairs_mode_matches_oracle(fmt, m, n, k, k_block, s, phi, accum):
+    """num_slices | PAIRS_ALL: all s*s slice pairs (the paper's setting), anti-diagonals 2s ... 2."""
+    A, B = inputs.phi_pair(m, n, k, phi, seed=m + 3 * n)
+    Ad, Bd = _upload(A, B)
+    Cd = torch.zeros((n, m), dtype=torch.float64, device="cuda")
+    ws = device.Workspace.for_problem(m, n, k, FMT[fmt], s | lib.PAIRS_ALL, k_block)
+    lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, FMT[fmt], s | lib.PAIRS_ALL, k_block, ACC[accum])
+    assert lib.ozaki_last_device_status() == 0
+    C = device.from_device_colmajor(Cd)
+    Cref, blocks = oz.ozaki_dgemm(A, B, fmt, s, k_block, mode="full", return_blocks=True)
+    assert np.array_equal(C.view(np.uint64), Cref.view(np.uint64))
+    if accum == "hw":
+        T, npairs = len(blocks), s * s
+        P = torch.zeros((T, npairs, n, m), dtype=torch.float32, device="cuda")
+        lib.ozaki_pair_products(m, n, k, Ad, m, Bd, k, FMT[fmt], s | lib.PAIRS_ALL, k_block, P)
+        torch.cuda.synchronize()
+        Pn = P.cpu().numpy()
+        b = oz.make_plan(k, fmt, k_block).b
+        for t, br in enumerate(blocks):
+            assert br.pairs == oz.pair_order(s, "full")
+            for z, Pref in enumerate(br.products):
+                assert np.array_equal(Pn[t, z], np.ldexp(Pref.astype(np.float64), -2 * b).astype(np.float32).T), (t, z)
     ws.close()
 
 

@@ -68,6 +68,9 @@ def test_workspace_sizes():
     assert lib.ozaki_workspace_bytes(16, 16, 1 << 20, 0, 4, 0) == 0     # block longer than the library supports
     assert lib.ozaki_workspace_bytes(16, 16, 1 << 20, 0, 4, 8192) > 0
     assert lib.ozaki_workspace_bytes(0, 0, 0, 0, 4, 0) >= 256
+    tri = lib.ozaki_workspace_bytes(1024, 1024, 1024, 0, 8, 0)
+    allp = lib.ozaki_workspace_bytes(1024, 1024, 1024, 0, 8 | lib.PAIRS_ALL, 0)
+    assert allp - tri == (64 - 36) * 1024 * 1024 * 4                   # s*s instead of s(s+1)/2 products
 
 
 def test_argument_errors_are_reported_before_anything_is_launched():
