@@ -8,13 +8,23 @@ given number, and fail loudly if there is none.
 FP8 E4M3 follows the OCP 8-bit floating point definition (1 sign, 4 exponent bits with
 bias 7, 3 fraction bits, no infinities, S.1111.111 is NaN, largest finite value 448),
 which is the flavour the gfx950 matrix unit consumes.
+
+FP6 E2M3 (Section 4.1 names FP6 as the format to try where it is twice as fast as FP8) is the
+OCP microscaling element format: 1 sign, 2 exponent bits with bias 1, 3 fraction bits, no
+infinities or NaNs; subnormals 0.125 .. 0.875, normals 1.0 .. 7.5.  It has the same four
+significand bits as E4M3, so the slices themselves are the same numbers q * 2^-b; but its
+smallest step is 1/8, so the stored code holds TWICE the value of Eq. 8 (q * 2^-(b-1), at
+most 2.0) and the factor 1/4 per product is applied with the exponents.
 """
 from __future__ import annotations
 
 import numpy as np
 
 #: significand bits including the hidden bit (the paper's m_Type2, Section 3)
-SIGNIFICAND_BITS = {"fp8": 4, "fp16": 11, "fp6_e3m2": 3}
+SIGNIFICAND_BITS = {"fp8": 4, "fp16": 11, "fp6": 4, "fp6_e3m2": 3}
+
+#: the stored code holds slice * 2^CODE_SHIFT (nonzero only for FP6 E2M3, see above)
+CODE_SHIFT = {"fp8": 0, "fp16": 0, "fp6": 1}
 
 
 def e4m3_decode_table() -> np.ndarray:
@@ -71,7 +81,47 @@ def fp16_decode(codes: np.ndarray) -> np.ndarray:
     return np.asarray(codes, dtype=np.uint16).view(np.float16).astype(np.float64)
 
 
+def e2m3_decode_table() -> np.ndarray:
+    """Value of each of the 64 OCP E2M3 codes."""
+    vals = np.empty(64, dtype=np.float64)
+    for code in range(64):
+        sign = -1.0 if code & 0x20 else 1.0
+        e = (code >> 3) & 0x3
+        f = code & 0x7
+        if e == 0:
+            vals[code] = sign * (f / 8.0) * 2.0 ** (1 - 1)          # subnormal
+        else:
+            vals[code] = sign * (1.0 + f / 8.0) * 2.0 ** (e - 1)    # normal
+    return vals
+
+
+_E2M3_VALUES = e2m3_decode_table()
+
+
+def e2m3_decode(codes: np.ndarray) -> np.ndarray:
+    return _E2M3_VALUES[np.asarray(codes, dtype=np.uint8)]
+
+
+def e2m3_encode_exact(values: np.ndarray) -> np.ndarray:
+    """6-bit codes (one per uint8) of `values`; every value must be exactly representable; zero -> 0."""
+    values = np.asarray(values, dtype=np.float64)
+    out = np.zeros(values.shape, dtype=np.uint8)
+    found = values == 0
+    for code in range(64):
+        if code in (0x00, 0x20):
+            continue
+        hit = values == _E2M3_VALUES[code]
+        out[hit] = code
+        found |= hit
+    if not found.all():
+        raise ValueError(f"value not representable in FP6 E2M3: {values[~found].ravel()[:4]}")
+    return out
+
+
 def encode_exact(fmt: str, values: np.ndarray) -> np.ndarray:
+    """Codes of the slice values `values` (= q * 2^-b, Eq. 8) in format `fmt`."""
+    if fmt == "fp6":
+        return e2m3_encode_exact(np.asarray(values, dtype=np.float64) * 2.0 ** CODE_SHIFT["fp6"])
     if fmt == "fp8":
         return e4m3_encode_exact(values)
     if fmt == "fp16":
@@ -80,6 +130,9 @@ def encode_exact(fmt: str, values: np.ndarray) -> np.ndarray:
 
 
 def decode(fmt: str, codes: np.ndarray) -> np.ndarray:
+    """Slice values (= q * 2^-b) of the codes."""
+    if fmt == "fp6":
+        return e2m3_decode(codes) * 2.0 ** -CODE_SHIFT["fp6"]
     if fmt == "fp8":
         return e4m3_decode(codes)
     if fmt == "fp16":

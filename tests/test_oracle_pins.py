@@ -4,6 +4,7 @@ Each test names the passage it pins.  None of them re-types the oracle's own for
 they use values the paper prints (Table 2, Section 5.4), exact rational arithmetic,
 the host FPU, an independent library conversion (torch's float8_e4m3fn) or closed forms.
 """
+import dataclasses
 import math
 import os
 from fractions import Fraction
@@ -110,7 +111,7 @@ def _nasty_rows(rng, rows, k):
     return X
 
 
-@pytest.mark.parametrize("fmt,k", [("fp8", 64), ("fp16", 64), ("fp16", 1024), ("fp8", 4096)])
+@pytest.mark.parametrize("fmt,k", [("fp8", 64), ("fp16", 64), ("fp16", 1024), ("fp8", 4096), ("fp6", 64), ("fp6", 4096)])
 def test_slices_sum_back_exactly_and_fit_their_format(fmt, k):
     rng = np.random.default_rng(11)
     X = _nasty_rows(rng, 12, k)
@@ -182,6 +183,50 @@ def test_e4m3_table_matches_torch_float8():
         formats.e4m3_encode_exact(np.array([17 / 16.0]))
 
 
+def test_e2m3_table_has_the_published_format_constants():
+    """OCP microscaling FP6 E2M3: bias 1, no infinities/NaNs, subnormals 0.125..0.875, normals 1.0..7.5."""
+    vals = formats.e2m3_decode(np.arange(64, dtype=np.uint8))
+    assert np.all(np.isfinite(vals))
+    pos = vals[:32]
+    assert np.array_equal(vals[32:], -pos)                                  # bit 5 is the sign
+    assert np.all(np.diff(pos) > 0)                                         # codes ordered like their values
+    assert pos[0] == 0.0 and pos[1] == 0.125 and pos[7] == 0.875            # subnormals: multiples of 1/8
+    assert pos[8] == 1.0 and pos[31] == 7.5                                 # smallest / largest normal
+    assert np.array_equal(pos[:16], np.arange(16) / 8.0)                    # step 1/8 up to 1.875
+    assert np.array_equal(pos[16:24], 2.0 + np.arange(8) / 4.0) and np.array_equal(pos[24:], 4.0 + np.arange(8) / 2.0)
+    # the 33 slice values q/16 are stored as q/8; q/16 itself is not representable for odd q
+    sl = np.arange(-16, 17) / 16.0
+    codes = formats.encode_exact("fp6", sl)
+    assert codes.max() < 64 and np.array_equal(formats.decode("fp6", codes), sl)
+    assert np.array_equal(formats.e2m3_decode(codes), 2.0 * sl)
+    with pytest.raises(ValueError):
+        formats.e2m3_encode_exact(np.array([1 / 16.0]))
+    with pytest.raises(ValueError):
+        formats.encode_exact("fp6", np.array([17 / 16.0]))
+
+
+def test_fp6_e2m3_has_the_slice_width_of_e4m3_and_gives_the_same_bits():
+    """Four significand bits either way (Eq. 2), so plan, slices, exponents, products and C coincide."""
+    for k, kb in ((8, 0), (4096, 0), (65536, 0), (262144, 0), (1000, 384)):
+        assert oz.make_plan(k, "fp6", kb) == dataclasses.replace(oz.make_plan(k, "fp8", kb), fmt="fp6")
+    assert oz.table2_slice_count(4096, formats.SIGNIFICAND_BITS["fp6"], 24) == 11          # the FP8 E4M3 column of Table 2
+    rng = np.random.default_rng(66)
+    A = inputs.phi_matrix(24, 200, 2.0, rng)
+    B = inputs.phi_matrix(200, 20, 2.0, rng)
+    for kb in (0, 64):
+        C8, blk8 = oz.ozaki_dgemm(A, B, "fp8", 9, kb, return_blocks=True)
+        C6, blk6 = oz.ozaki_dgemm(A, B, "fp6", 9, kb, return_blocks=True)
+        assert np.array_equal(C8.view(np.uint64), C6.view(np.uint64))
+        for b8, b6 in zip(blk8, blk6):
+            assert all(np.array_equal(x, y) for x, y in zip(b8.products, b6.products))
+    c8, e8, _ = oz.split_operand(A, "fp8", 9, 64)
+    c6, e6, _ = oz.split_operand(A, "fp6", 9, 64)
+    for t in range(len(c8)):
+        for p in range(9):
+            assert np.array_equal(formats.decode("fp8", c8[t][p]), formats.decode("fp6", c6[t][p]))
+            assert np.array_equal(e8[t][p], e6[t][p])
+
+
 # ------------------------------------------------------------------ Eq. 10-11
 def _exact_sum_of_terms(blocks, b):
     """sum over blocks and pairs of 2^(cA+cB-2b) * P in exact rational arithmetic."""
@@ -196,7 +241,7 @@ def _exact_sum_of_terms(blocks, b):
     return tot
 
 
-@pytest.mark.parametrize("fmt,kblock", [("fp8", 0), ("fp16", 0), ("fp8", 16), ("fp16", 10)])
+@pytest.mark.parametrize("fmt,kblock", [("fp8", 0), ("fp16", 0), ("fp8", 16), ("fp16", 10), ("fp6", 0), ("fp6", 16)])
 def test_all_slices_all_pairs_equal_the_exact_product(fmt, kblock):
     """Eq. 10 with every slice and every pair is an identity: brute force on tiny, non-square inputs."""
     rng = np.random.default_rng(21)
