@@ -33,7 +33,12 @@ extern "C" {
 /* Type2 of the paper (Section 3): storage format of the slices = input format of the matrix unit. */
 enum {
     OZAKI_SLICE_FP8_E4M3 = 0, /* OCP E4M3, 4 significand bits, FP32 accumulation (Section 4.1)        */
-    OZAKI_SLICE_FP16 = 1      /* IEEE binary16, 11 significand bits, FP32 accumulation (Section 4.1)  */
+    OZAKI_SLICE_FP16 = 1,     /* IEEE binary16, 11 significand bits, FP32 accumulation (Section 4.1)  */
+    OZAKI_SLICE_FP6_E2M3 = 2  /* OCP microscaling FP6 E2M3 (bias 1, no Inf/NaN): the 4 significand bits */
+                              /* of E4M3, so the same slices and the same C as OZAKI_SLICE_FP8_E4M3,    */
+                              /* on the twice as fast FP6 path of the matrix unit that Section 4.1      */
+                              /* points to.  E2M3's smallest step is 1/8: a code holds twice the value  */
+                              /* of Eq. 8, and the factor 1/4 per product is applied with the exponents */
 };
 
 /* How the slice-pair products are summed into FP64 (Section 3 after Eq. 11; Section 4.2). */
@@ -148,8 +153,9 @@ int ozaki_profile_read(float* ms_out, int* launches_out);
  *   X, ldx      DEVICE, column-major
  *   slices_out  DEVICE: T*s matrices in the order [block t][slice p], each `rows` vectors of
  *               kb_t = min(k_block, k - t*k_block) entries, vector-major (entry kk of vector r at
- *               r*kb_t + kk); 1 byte per entry (E4M3 code) or 2 bytes (binary16 bits).  Blocks are
- *               packed back to back (block t starts after s*rows*kb_u entries of every earlier block u).
+ *               r*kb_t + kk); 1 byte per entry (E4M3 code, or E2M3 code in the low six bits) or 2 bytes
+ *               (binary16 bits).  Blocks are packed back to back (block t starts after s*rows*kb_u
+ *               entries of every earlier block u).
  *   exps_out    DEVICE: int32 [T][s][rows], the exponents c of Eq. 4
  */
 int ozaki_split(int is_B, int64_t rows, int64_t k, const double* X, int64_t ldx,
@@ -160,7 +166,8 @@ int ozaki_split(int is_B, int64_t rows, int64_t k, const double* X, int64_t ldx,
  * ozaki_pair_products -- the FP32 slice-pair products of Eq. 10-11, as the matrix unit produced them.
  *   P_out  DEVICE: float [T][pairs][n][m]: for block t and pair index z (pairs in accumulation order:
  *          anti-diagonals g = p+q from s+1 down to 2, p ascending within one), an m x n column-major
- *          matrix (leading dimension m) holding sum_kk sliceA_p(i,kk) * sliceB_q(kk,j).
+ *          matrix (leading dimension m) holding sum_kk sliceA_p(i,kk) * sliceB_q(kk,j), the slices
+ *          being the values of Eq. 8 (for FP6 the matrix unit's result times the exact factor 1/4).
  */
 int ozaki_pair_products(int64_t m, int64_t n, int64_t k,
                         const double* A, int64_t lda, const double* B, int64_t ldb,

@@ -13,7 +13,9 @@
 // Scaling by a power of two commutes with rounding (inside the normal range), so summing with exponents
 // relative to the first slice and rescaling once gives the same bits as scaling every term by
 // 2^(cA_p + cB_q) as Eq. 10 writes it.  P_pq is the FP32 value left by the matrix unit; it already
-// contains the factor 2^-2b of the two slice entries and is an exact integer multiple of 2^-2b.
+// contains the factor 2^-2b of the two slice entries and is an exact integer multiple of 2^-2b.  (FP6 codes
+// hold twice the slice value: the stored product is four times too large, an integer multiple of 2^-(2b-2); it
+// is read as that integer and still weighted 2^-2b.)
 //
 // Two instantiations: hardware FP64 (int->double convert, ldexp, add -- no multiply) and integer-only
 // (fp64_emu.hpp), which executes no FP64 instruction at all and returns the same bits.
@@ -41,7 +43,8 @@ struct AccArgs {
     int64_t rows_pad_a, rows_pad_b;
     int64_t m, n;
     int tiles_m, tiles_n;
-    int two_b;               // 2b: the products are integer multiples of 2^-two_b
+    int two_b;               // 2b: a term is (stored product) * 2^(p_frac - two_b) * 2^e
+    int p_frac;              // the stored products are integer multiples of 2^-p_frac (2b; 2b - 2 for FP6 codes)
     int read_S, write_S, add_to_C;
     int allow_chain;
     const int32_t* da;       // deltas of the block: [tiles_m][s]
@@ -139,7 +142,7 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int e = eA + (q == 0 ? 0 : relB[q][nl + r]);
-            const int iv = fp32_bits_to_scaled_int(vv[r], a.two_b);
+            const int iv = fp32_bits_to_scaled_int(vv[r], a.p_frac);
             if (!first && e == run_e[r]) {
                 run_sum[r] += iv;
             } else {
@@ -195,7 +198,7 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
 }
 
 __global__ void __launch_bounds__(256) export_products_kernel(const float* __restrict__ P, float* __restrict__ out, int64_t m,
-                                                              int64_t n, int tiles_m, int tiles_n) {
+                                                              int64_t n, int tiles_m, int tiles_n, float factor) {
     // one thread per stored float; grid.y = pair
     const size_t pair_stride = (size_t)tiles_m * tiles_n * TILE_ELEMS;
     const int64_t z = blockIdx.y;
@@ -205,7 +208,7 @@ __global__ void __launch_bounds__(256) export_products_kernel(const float* __res
         int ml, nl;
         acc_order_to_mn(idx, ml, nl);
         const int64_t mi = (int64_t)tm * TILE + ml, nj = (int64_t)tn * TILE + nl;
-        if (mi < m && nj < n) out[((size_t)z * n + nj) * m + mi] = P[(size_t)z * pair_stride + g];
+        if (mi < m && nj < n) out[((size_t)z * n + nj) * m + mi] = P[(size_t)z * pair_stride + g] * factor;   // power of two: exact
     }
 }
 
@@ -240,6 +243,7 @@ hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B,
     a.rows_pad_a = A.rows_pad; a.rows_pad_b = B.rows_pad;
     a.m = pl.m; a.n = pl.n; a.tiles_m = (int)pl.tiles_m; a.tiles_n = (int)pl.tiles_n;
     a.two_b = 2 * pl.b;
+    a.p_frac = pl.p_frac;
     a.allow_chain = 1;
     a.da = A.deltas + (size_t)t * pl.tiles_m * pl.s;
     a.db = B.deltas + (size_t)t * pl.tiles_n * pl.s;
@@ -257,7 +261,8 @@ hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B,
 hipError_t launch_export_products(const Plan& pl, int nz, const float* P, float* out, hipStream_t st) {
     if (nz <= 0 || pl.m == 0 || pl.n == 0) return hipSuccess;
     dim3 grid(grid_for(pl.tiles_m * pl.tiles_n * (int64_t)TILE_ELEMS), (unsigned)nz);
-    hipLaunchKernelGGL(export_products_kernel, grid, dim3(256), 0, st, P, out, pl.m, pl.n, (int)pl.tiles_m, (int)pl.tiles_n);
+    const float factor = ldexpf(1.0f, pl.p_frac - 2 * pl.b);
+    hipLaunchKernelGGL(export_products_kernel, grid, dim3(256), 0, st, P, out, pl.m, pl.n, (int)pl.tiles_m, (int)pl.tiles_n, factor);
     return hipGetLastError();
 }
 

@@ -12,18 +12,29 @@ constexpr int64_t MAX_K_BLOCK = 32768;
 
 // ---- tiling of the slice-pair GEMM: one workgroup computes one TILE x TILE block of one pair product ------
 constexpr int TILE = 256;
-constexpr int CHUNK_BYTES = 64;           // bytes of the inner dimension per row staged per pipeline step
+constexpr int CHUNK_BYTES = 64;           // bytes of the inner dimension per row staged per pipeline step (FP8, FP16)
+constexpr int CHUNK_BYTES_FP6 = 48;       // the same 64 inner indices as 6-bit codes
 constexpr int TILE_ELEMS = TILE * TILE;
+
+// slice formats (values of ozaki_slice_format)
+constexpr int FMT_FP8 = 0, FMT_FP16 = 1, FMT_FP6 = 2;
 
 // ---- slice storage ---------------------------------------------------------------------------------------
 // One slice matrix (block t, slice p) of an operand is stored as [chunk kc][vector r][CHUNK_BYTES]:
 // the 256 vectors a workgroup stages for one pipeline step are 16 KiB of contiguous memory.  The number
 // of vectors is padded to a multiple of TILE and every block to whole chunks; the padding holds zero
 // codes, which contribute exact zeros to every product.
+//
+// FP6: a chunk holds 64 inner indices of every vector as 6-bit codes.  The matrix unit wants the 32 codes of a
+// vector's k-group g (inner indices 32g .. 32g+31 of the chunk) as one 192-bit little-endian string (code i at
+// bits 6i .. 6i+5).  A chunk stores the first 16 bytes and the last 8 bytes of these strings in four planes,
+//     [g = 0: rows_pad x 16 B][g = 1: rows_pad x 16 B][g = 0: rows_pad x 8 B][g = 1: rows_pad x 8 B]
+// (rows_pad x 48 bytes in all), so that the part of a plane that belongs to a 256-vector tile is contiguous and a
+// wave's fragment reads from the staged copy are contiguous, bank-conflict-free 128- and 64-bit accesses.
 struct Operand {
     int64_t rows;         // real vectors: m for A (its rows), n for B (its columns)
     int64_t rows_pad;     // multiple of TILE
-    uint8_t* slices;      // [T][s][chunks][rows_pad][CHUNK_BYTES]
+    uint8_t* slices;      // [T][s][chunks][rows_pad][row_bytes]
     int32_t* exps;        // [T][s][rows_pad]   exponent c of Eq. 4 (0 for padding vectors)
     int32_t* deltas;      // [T][rows_pad/TILE][s]  per 256-vector tile and slice p: c_p - c_(p+1) if that difference
                           //                        is the same for all real vectors of the tile, else DELTA_IRREGULAR
@@ -33,8 +44,11 @@ constexpr int DELTA_IRREGULAR = -2147483647 - 1;
 
 struct Plan {
     int64_t m, n, k;
-    int fmt;              // 0 = FP8 E4M3, 1 = FP16
-    int elem_bytes;
+    int fmt;              // FMT_FP8, FMT_FP16, FMT_FP6
+    int epc;              // inner indices per chunk: 64 (FP8, FP6) or 32 (FP16)
+    int row_bytes;        // bytes of one vector in one chunk: 64 (FP8, FP16) or 48 (FP6)
+    int p_frac;           // a stored pair product is an integer multiple of 2^-p_frac: 2b, for FP6 (whose codes hold
+                          // twice the slice value) 2b - 2; the true product is the stored one times 2^(p_frac - 2b)
     int s;                // slices per operand
     int b;                // magnitude bits of a slice entry (53 - rho)
     int rho;

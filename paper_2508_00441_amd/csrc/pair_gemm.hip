@@ -1,7 +1,8 @@
 // Slice-pair GEMMs on the gfx950 matrix unit (paper Section 3, Eq. 10-11; Section 4.1).
 //
 // For one k-block and one slice pair (p, q) the product  P[i][j] = sum_kk sliceA_p[i][kk] * sliceB_q[j][kk]
-// is formed with FP8 (v_mfma_f32_32x32x64_f8f6f4) or FP16 (v_mfma_f32_32x32x16_f16) inputs and FP32
+// is formed with FP8 or FP6 (v_mfma_f32_32x32x64_f8f6f4; FP6 codes hold twice the slice value, which the
+// accumulation kernel undoes with the exponents) or FP16 (v_mfma_f32_32x32x16_f16) inputs and FP32
 // accumulation.  Every slice entry is q*2^-b with |q| <= 2^b and k_block*4^b <= 2^24, so every partial sum
 // is an integer multiple of 2^-2b below 2^(24-2b) in magnitude and the FP32 accumulation is exact (Eq. 11).
 // Because the sum is exact, the order in which the inner index is consumed is irrelevant; the kernel
@@ -27,6 +28,10 @@
 // so that the 16 lanes served together by a 128-bit LDS read hit 64 distinct banks.  A direct-to-LDS load
 // writes lane L's 16 bytes at (wave-uniform base) + 16 L, so the swizzle is applied on the global side: each
 // lane fetches the piece that belongs at its fixed LDS position.
+//
+// FP6 stages are 48 bytes per vector, kept in the four planes of the slice layout ([k-group][vector][16 B] and
+// [k-group][vector][8 B]): every plane of a tile is contiguous in memory, is copied as it is, and a wave's fragment
+// reads (one 128-bit and one 64-bit read per 32 x 64 operand tile) are contiguous, so no swizzle is needed.
 #include <type_traits>
 
 #include "layout.hpp"
@@ -35,6 +40,7 @@ namespace ozaki {
 
 namespace {
 
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -42,7 +48,7 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 
 struct GemmArgs {
-    const uint8_t* sa;       // A slices of the block: [s][chunks][rows_pad_a][CHUNK_BYTES]
+    const uint8_t* sa;       // A slices of the block: [s][chunks][rows_pad_a][row bytes]
     const uint8_t* sb;       // B slices of the block
     float* P;                // [nz][tiles_n][tiles_m][TILE_ELEMS]
     int64_t rows_pad_a, rows_pad_b;
@@ -55,11 +61,8 @@ struct GemmArgs {
     Pass pass;
 };
 
-constexpr int BK = CHUNK_BYTES;                       // bytes of the inner dimension per row and stage
 constexpr int NSTAGE = 4;
-constexpr int STAGE_BYTES = 2 * TILE * BK;            // X tile + Y tile
-constexpr int LPW = TILE * BK / 1024 / 4;             // direct-to-LDS load instructions per wave, operand and stage
-static_assert(BK == 64, "the swizzle and the fragment addressing below assume 64-byte LDS rows");
+static_assert(CHUNK_BYTES == 64, "the swizzle and the fragment addressing below assume 64-byte LDS rows");
 
 #define OZAKI_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define OZAKI_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
@@ -76,10 +79,16 @@ __device__ __forceinline__ void wait_and_barrier() {
     asm volatile("" ::: "memory");
 }
 
-template <bool FP16>
+template <int FMT>
 __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
-    constexpr int KS = FP16 ? 2 : 1;                  // MFMA k-steps per stage (32 resp. 64 bytes of k each)
-    constexpr int READS = FP16 ? 8 : 16;              // 128-bit LDS reads per wave and k-step
+    constexpr bool FP16 = FMT == FMT_FP16;
+    constexpr bool FP6 = FMT == FMT_FP6;
+    constexpr int BK = FP6 ? CHUNK_BYTES_FP6 : CHUNK_BYTES;   // bytes of the inner dimension per vector and stage
+    constexpr int OPERAND_BYTES = TILE * BK;          // one operand's share of a stage
+    constexpr int STAGE_BYTES = 2 * OPERAND_BYTES;    // X tile + Y tile
+    constexpr int LPW = OPERAND_BYTES / 1024 / 4;     // direct-to-LDS load instructions per wave, operand and stage
+    constexpr int KS = FP16 ? 2 : 1;                  // MFMA k-steps per stage (32 resp. 64 inner indices each)
+    constexpr int READS = FP16 ? 8 : 16;              // LDS read instructions per wave and k-step
     __shared__ __attribute__((aligned(16))) uint8_t lds[NSTAGE * STAGE_BYTES];
 
     const int tid = threadIdx.x;
@@ -105,21 +114,44 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
         for (int j = 0; j + 1 < glen; ++j) links |= pair_linked(dA, dB, p0 + j, q0 - j) ? (1u << j) : 0u;
     }
 
-    // loader: a wave instruction fills 16 consecutive LDS rows; lane -> row lane/4, physical piece lane%4,
-    // which must hold logical piece (lane%4) ^ ((row>>2)&3); the row group starts at a multiple of 16 rows.
-    const unsigned lrow = lane >> 2, lpc = lane & 3;
-    const unsigned goff = lrow * BK + ((lpc ^ ((lrow >> 2) & 3)) << 4);
-    const size_t cs_x = (size_t)a.rows_pad_b * BK, cs_y = (size_t)a.rows_pad_a * BK;
-    const uint8_t* const xtile = a.sb + (size_t)tn * TILE * BK + (size_t)wave * LPW * 1024 + goff;
-    const uint8_t* const ytile = a.sa + (size_t)tm * TILE * BK + (size_t)wave * LPW * 1024 + goff;
+    // loader.  FP8/FP16: a wave instruction fills 16 consecutive LDS rows; lane -> row lane/4, physical piece lane%4,
+    // which must hold logical piece (lane%4) ^ ((row>>2)&3); the row group starts at a multiple of 16 rows; a wave's
+    // LPW instructions cover consecutive kilobytes of the tile.  FP6: every instruction copies one kilobyte of one
+    // plane as it is; wave w takes kilobyte w of either 16-byte plane (4 KiB per tile each) and kilobyte w of the two
+    // 8-byte planes taken together (2 KiB per tile each).
+    const size_t cs_x = (size_t)a.rows_pad_b * BK, cs_y = (size_t)a.rows_pad_a * BK;      // chunk strides
+    const uint8_t* xtile;
+    const uint8_t* ytile;
+    size_t xpiece[LPW], ypiece[LPW];                  // byte offset of the wave's i-th instruction from xptr / yptr
+    if constexpr (FP6) {
+        xtile = a.sb + lane * 16;
+        ytile = a.sa + lane * 16;
+        const size_t rb = (size_t)a.rows_pad_b, ra = (size_t)a.rows_pad_a;
+        xpiece[0] = (size_t)tn * TILE * 16 + wave * 1024;
+        xpiece[1] = rb * 16 + xpiece[0];
+        xpiece[2] = rb * 32 + (size_t)(wave >> 1) * rb * 8 + (size_t)tn * TILE * 8 + (wave & 1) * 1024;
+        ypiece[0] = (size_t)tm * TILE * 16 + wave * 1024;
+        ypiece[1] = ra * 16 + ypiece[0];
+        ypiece[2] = ra * 32 + (size_t)(wave >> 1) * ra * 8 + (size_t)tm * TILE * 8 + (wave & 1) * 1024;
+    } else {
+        const unsigned lrow = lane >> 2, lpc = lane & 3;
+        const unsigned goff = lrow * BK + ((lpc ^ ((lrow >> 2) & 3)) << 4);
+        xtile = a.sb + (size_t)tn * TILE * BK + (size_t)wave * LPW * 1024 + goff;
+        ytile = a.sa + (size_t)tm * TILE * BK + (size_t)wave * LPW * 1024 + goff;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) xpiece[i] = ypiece[i] = (size_t)i * 1024;
+    }
+    // where the wave's i-th instruction lands inside an operand's share of a stage
+    auto lds_piece = [&](int i) -> int { return FP6 ? i * 4096 + wave * 1024 : (wave * LPW + i) * 1024; };
     const uint8_t* xptr;
     const uint8_t* yptr;
 
     // fragments: lane reads row lane%32 of each 32-row MFMA tile; lane/32 selects the k-group
     const int frow = lane & 31, fg = lane >> 5;
     const int fsw = (frow >> 2) & 3;
-    const int xbase = (wn * 128 + frow) * BK;
-    const int ybase = TILE * BK + (wm * 128 + frow) * BK;
+    const int xrow = wn * 128 + frow, yrow = wm * 128 + frow;
+    const int xbase = xrow * BK;
+    const int ybase = OPERAND_BYTES + yrow * BK;
 
     v16f acc[4][4];
     auto zero_acc = [&]() {
@@ -153,13 +185,13 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
     yptr = ytile + (size_t)p0 * chunks * cs_y;
     const size_t x_wrap = (size_t)(2 * chunks - 1) * cs_x;
     auto issue_next = [&](int buf) {
-        uint8_t* lb = lds + buf * STAGE_BYTES + wave * LPW * 1024;
+        uint8_t* lb = lds + buf * STAGE_BYTES;
 #pragma unroll
         for (int i = 0; i < LPW; ++i)
-            __builtin_amdgcn_global_load_lds(OZAKI_GPTR(xptr + i * 1024), OZAKI_LPTR(lb + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(OZAKI_GPTR(xptr + xpiece[i]), OZAKI_LPTR(lb + lds_piece(i)), 16, 0, 0);
 #pragma unroll
         for (int i = 0; i < LPW; ++i)
-            __builtin_amdgcn_global_load_lds(OZAKI_GPTR(yptr + i * 1024), OZAKI_LPTR(lb + TILE * BK + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(OZAKI_GPTR(yptr + ypiece[i]), OZAKI_LPTR(lb + OPERAND_BYTES + lds_piece(i)), 16, 0, 0);
         // branch-free pointer update (a branch here would split the k-step's basic block and with it the
         // instruction interleaving)
         const bool adv = issued + 1 < total;
@@ -182,6 +214,27 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
             for (int i = 0; i < 4; ++i) xf[fb][i] = *reinterpret_cast<const v8h*>(base + xbase + i * 32 * BK + c0);
 #pragma unroll
             for (int j = 0; j < 4; ++j) yf[fb][j] = *reinterpret_cast<const v8h*>(base + ybase + j * 32 * BK + c0);
+        } else if constexpr (FP6) {
+            // 24 bytes per lane: 16 from the 16-byte plane of its k-group, 8 from the 8-byte plane; the last two
+            // registers of the operand are not read by the instruction for 6-bit formats
+            const uint8_t* x16 = base + fg * 4096 + xrow * 16;
+            const uint8_t* y16 = base + OPERAND_BYTES + fg * 4096 + yrow * 16;
+            const unsigned x8 = (unsigned)(uintptr_t)OZAKI_LPTR(base + 8192 + fg * 2048 + xrow * 8);
+            const unsigned y8 = (unsigned)(uintptr_t)OZAKI_LPTR(base + OPERAND_BYTES + 8192 + fg * 2048 + yrow * 8);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                // every 64-bit read gets an address register of its own (the empty asm hides their common origin):
+                // merged into two-address reads they would land in registers that belong to two different operands
+                // and would have to be moved, with a wait for the LDS in the middle of the k-step
+                unsigned ax = x8 + i * 32 * 8, ay = y8 + i * 32 * 8;
+                asm volatile("" : "+v"(ax), "+v"(ay));
+                const v4i xlo = *reinterpret_cast<const v4i*>(x16 + i * 32 * 16);
+                const v2i xhi = *reinterpret_cast<const __attribute__((address_space(3))) v2i*>((uintptr_t)ax);
+                xf[fb][i] = __builtin_shufflevector(xlo, __builtin_shufflevector(xhi, xhi, 0, 1, -1, -1), 0, 1, 2, 3, 4, 5, -1, -1);
+                const v4i ylo = *reinterpret_cast<const v4i*>(y16 + i * 32 * 16);
+                const v2i yhi = *reinterpret_cast<const __attribute__((address_space(3))) v2i*>((uintptr_t)ay);
+                yf[fb][i] = __builtin_shufflevector(ylo, __builtin_shufflevector(yhi, yhi, 0, 1, -1, -1), 0, 1, 2, 3, 4, 5, -1, -1);
+            }
         } else {
             const int c0 = ((2 * fg) ^ fsw) << 4, c1 = ((2 * fg + 1) ^ fsw) << 4;
 #pragma unroll
@@ -204,6 +257,7 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 if constexpr (FP16) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf[fb][i], yf[fb][j], acc[i][j], 0, 0, 0);
+                else if constexpr (FP6) acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xf[fb][i], yf[fb][j], acc[i][j], 2, 2, 0, 0, 0, 0);
                 else acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xf[fb][i], yf[fb][j], acc[i][j], 0, 0, 0, 0, 0, 0);
             }
     };
@@ -237,7 +291,7 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
         for (int i = 0; i < 16; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                    // one MFMA
             if (i < 8) __builtin_amdgcn_sched_group_barrier(0x100, READS / 8, 0);                 // LDS reads
-            else if (last_of_stage) __builtin_amdgcn_sched_group_barrier(0x020, 2 * LPW / 8, 0);  // VMEM reads
+            else if (last_of_stage && i - 8 < 2 * LPW) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // a VMEM read
         }
         if constexpr (last_of_stage) ++stage;
     };
@@ -290,7 +344,7 @@ hipError_t launch_pair_gemm(const Plan& pl, const Operand& A, const Operand& B, 
                             bool allow_chain, int64_t t, float* P, hipStream_t st) {
     if (ps.ngroups <= 0 || pl.tiles_m == 0 || pl.tiles_n == 0 || pl.chunks == 0) return hipSuccess;
     GemmArgs a;
-    const size_t slice_a = (size_t)pl.chunks * A.rows_pad * CHUNK_BYTES, slice_b = (size_t)pl.chunks * B.rows_pad * CHUNK_BYTES;
+    const size_t slice_a = (size_t)pl.chunks * A.rows_pad * pl.row_bytes, slice_b = (size_t)pl.chunks * B.rows_pad * pl.row_bytes;
     a.sa = A.slices + (size_t)t * pl.s * slice_a;
     a.sb = B.slices + (size_t)t * pl.s * slice_b;
     a.P = P;
@@ -302,8 +356,9 @@ hipError_t launch_pair_gemm(const Plan& pl, const Operand& A, const Operand& B, 
     a.order = order; a.pass = ps;
     const int64_t blocks = (int64_t)ps.ngroups * pl.tiles_m * pl.tiles_n;
     if (blocks > 0x7FFFFFFF || pl.chunks > 0x7FFFFFFF) return hipErrorInvalidValue;
-    if (pl.fmt == 1) hipLaunchKernelGGL((pair_gemm_kernel<true>), dim3((unsigned)blocks), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((pair_gemm_kernel<false>), dim3((unsigned)blocks), dim3(256), 0, st, a);
+    if (pl.fmt == FMT_FP16) hipLaunchKernelGGL((pair_gemm_kernel<FMT_FP16>), dim3((unsigned)blocks), dim3(256), 0, st, a);
+    else if (pl.fmt == FMT_FP6) hipLaunchKernelGGL((pair_gemm_kernel<FMT_FP6>), dim3((unsigned)blocks), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((pair_gemm_kernel<FMT_FP8>), dim3((unsigned)blocks), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 

@@ -71,11 +71,23 @@ __device__ __forceinline__ uint32_t encode_type2_pair(int q0, int q1, int b) {
     }
 }
 
-template <int U, int TPR, bool FP16>
+// FP6 E2M3 code of q * 2^-(b-1), twice the slice value (|q| <= 2^b, b <= 4): with q' = q * 2^(4-b) the value is q'/8,
+// and for magnitudes 0..16 the code (subnormals 0..7, normals 8..15 with exponent field 1, 16 = 2.0) is the magnitude
+// itself; bit 5 is the sign.
+__device__ __forceinline__ uint32_t encode_e2m3(int q, int b) {
+    const int v = q << (4 - b);
+    const uint32_t mag = (uint32_t)(v < 0 ? -v : v);
+    return mag | (v < 0 ? 32u : 0u);
+}
+
+template <int U, int TPR, int FMT>
 __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArgs a) {
+    constexpr bool FP16 = FMT == FMT_FP16;
+    constexpr bool FP6 = FMT == FMT_FP6;
     constexpr int BLOCK = TPR < 256 ? 256 : TPR;
     constexpr int RPB = BLOCK / TPR;                  // vectors per workgroup
     constexpr int EPC = FP16 ? CHUNK_BYTES / 2 : CHUNK_BYTES;   // elements per chunk
+    constexpr int ROWB = FP6 ? CHUNK_BYTES_FP6 : CHUNK_BYTES;   // bytes per vector and chunk
     constexpr int WAVES_PER_ROW = TPR / 64;
     constexpr int ACTIVE = 0x7FFF;
     __shared__ int red[2][BLOCK / 64];
@@ -162,7 +174,7 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
         c_prev = c;
 
         // ---- Eq. 5-8 element by element, eight codes per store
-        uint8_t* const dst_slice = a.slices + (size_t)((t * a.s + p) * a.chunks) * (size_t)a.rows_pad * CHUNK_BYTES;
+        uint8_t* const dst_slice = a.slices + (size_t)((t * a.s + p) * a.chunks) * (size_t)a.rows_pad * ROWB;
         uint64_t rmax = 0;                                             // largest |remainder| of this thread's active elements
         int cdorm = NO_ELEM;                                           // largest cd of its still dormant elements
         const int64_t round_bias = ((int64_t)1 << (F - 1)) - 1;
@@ -218,25 +230,46 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
                 }
                 qs[e] = q;
             }
-            uint32_t c2[4];                                            // two codes each
-#pragma unroll
-            for (int e = 0; e < 4; ++e) c2[e] = encode_type2_pair<FP16>(qs[2 * e], qs[2 * e + 1], a.b);
             const int64_t ke = 8 * ((int64_t)tr + (int64_t)TPR * u);
-            if (ke < padded) {
-                const int64_t kc = ke / EPC;
-                uint8_t* dst = dst_slice + ((size_t)kc * a.rows_pad + row) * CHUNK_BYTES + (ke % EPC) * (FP16 ? 2 : 1);
-                if (FP16) {
-                    uint4 w;
-                    w.x = c2[0];
-                    w.y = c2[1];
-                    w.z = c2[2];
-                    w.w = c2[3];
-                    *reinterpret_cast<uint4*>(dst) = w;
-                } else {
-                    uint2 w;
-                    w.x = c2[0] | (c2[1] << 16);
-                    w.y = c2[2] | (c2[3] << 16);
-                    *reinterpret_cast<uint2*>(dst) = w;
+            if constexpr (FP6) {
+                // eight 6-bit codes = 48 bits: octet j of the 24-byte string of k-group g, i.e. bytes
+                // 6j .. 6j+5 of the string, whose first 16 bytes live in the 16-byte plane of g and the rest in the
+                // 8-byte plane (see layout.hpp).  Written as one 32-bit and one 16-bit store, both naturally aligned.
+                uint64_t w48 = 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) w48 |= (uint64_t)encode_e2m3(qs[e], a.b) << (6 * e);
+                if (ke < padded) {
+                    const int64_t kc = ke / EPC;
+                    const int o = (int)((ke % EPC) / 8), g = o >> 2, j = o & 3;
+                    uint8_t* const chunk = dst_slice + (size_t)kc * a.rows_pad * ROWB;
+                    uint8_t* const p16 = chunk + ((size_t)g * a.rows_pad + row) * 16;
+                    uint8_t* const p8 = chunk + (size_t)a.rows_pad * 32 + ((size_t)g * a.rows_pad + row) * 8;
+                    uint8_t* d32 = j == 0 ? p16 : j == 1 ? p16 + 8 : j == 2 ? p16 + 12 : p8 + 4;
+                    uint8_t* d16 = j == 0 ? p16 + 4 : j == 1 ? p16 + 6 : j == 2 ? p8 : p8 + 2;
+                    const bool low32 = (j & 1) == 0;                   // bytes 6j.. start 4-byte aligned for even j
+                    *reinterpret_cast<uint32_t*>(d32) = low32 ? (uint32_t)w48 : (uint32_t)(w48 >> 16);
+                    *reinterpret_cast<uint16_t*>(d16) = low32 ? (uint16_t)(w48 >> 32) : (uint16_t)w48;
+                }
+            } else {
+                uint32_t c2[4];                                            // two codes each
+#pragma unroll
+                for (int e = 0; e < 4; ++e) c2[e] = encode_type2_pair<FP16>(qs[2 * e], qs[2 * e + 1], a.b);
+                if (ke < padded) {
+                    const int64_t kc = ke / EPC;
+                    uint8_t* dst = dst_slice + ((size_t)kc * a.rows_pad + row) * CHUNK_BYTES + (ke % EPC) * (FP16 ? 2 : 1);
+                    if (FP16) {
+                        uint4 w;
+                        w.x = c2[0];
+                        w.y = c2[1];
+                        w.z = c2[2];
+                        w.w = c2[3];
+                        *reinterpret_cast<uint4*>(dst) = w;
+                    } else {
+                        uint2 w;
+                        w.x = c2[0] | (c2[1] << 16);
+                        w.y = c2[2] | (c2[3] << 16);
+                        *reinterpret_cast<uint2*>(dst) = w;
+                    }
                 }
             }
         }
@@ -251,22 +284,37 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
     }
 }
 
-template <bool FP16>
+template <int FMT>
 __global__ void __launch_bounds__(256) export_slices_kernel(const uint8_t* __restrict__ slices, int64_t rows, int64_t rows_pad,
                                                             int64_t k, int64_t kb, int64_t chunks, int s, void* out) {
     // plain layout: block t starts at s*rows*(t*kb) entries; inside, [p][row][kb_t]
+    constexpr bool FP16 = FMT == FMT_FP16;
+    constexpr bool FP6 = FMT == FMT_FP6;
     constexpr int EPC = FP16 ? CHUNK_BYTES / 2 : CHUNK_BYTES;
+    constexpr int ROWB = FP6 ? CHUNK_BYTES_FP6 : CHUNK_BYTES;
     const int64_t t = blockIdx.z, p = blockIdx.y;
     int64_t klen = k - t * kb;
     if (klen > kb) klen = kb;
     const int64_t total = rows * klen;
-    const uint8_t* src = slices + (size_t)((t * s + p) * chunks) * (size_t)rows_pad * CHUNK_BYTES;
+    const uint8_t* src = slices + (size_t)((t * s + p) * chunks) * (size_t)rows_pad * ROWB;
     const size_t out_base = (size_t)s * rows * (t * kb) + (size_t)p * rows * klen;
     for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
         const int64_t r = idx / klen, kk = idx % klen;
-        const size_t off = ((size_t)(kk / EPC) * rows_pad + r) * CHUNK_BYTES + (kk % EPC) * (FP16 ? 2 : 1);
-        if (FP16) reinterpret_cast<uint16_t*>(out)[out_base + idx] = *reinterpret_cast<const uint16_t*>(src + off);
-        else reinterpret_cast<uint8_t*>(out)[out_base + idx] = src[off];
+        if constexpr (FP6) {
+            // code i of k-group g sits at bits 6i .. 6i+5 of a 24-byte string: bytes 0..15 in the 16-byte plane of g,
+            // bytes 16..23 in its 8-byte plane
+            const uint8_t* chunk = src + (size_t)(kk / EPC) * rows_pad * ROWB;
+            const int e = (int)(kk % EPC), g = e >> 5, bit = (e & 31) * 6;
+            const uint8_t* p16 = chunk + ((size_t)g * rows_pad + r) * 16;
+            const uint8_t* p8 = chunk + (size_t)rows_pad * 32 + ((size_t)g * rows_pad + r) * 8;
+            const int b0 = bit >> 3, b1 = (bit + 5) >> 3;
+            const uint32_t lo = b0 < 16 ? p16[b0] : p8[b0 - 16], hi = b1 < 16 ? p16[b1] : p8[b1 - 16];
+            reinterpret_cast<uint8_t*>(out)[out_base + idx] = (uint8_t)((((hi << 8) | lo) >> (bit & 7)) & 63u);
+        } else {
+            const size_t off = ((size_t)(kk / EPC) * rows_pad + r) * CHUNK_BYTES + (kk % EPC) * (FP16 ? 2 : 1);
+            if (FP16) reinterpret_cast<uint16_t*>(out)[out_base + idx] = *reinterpret_cast<const uint16_t*>(src + off);
+            else reinterpret_cast<uint8_t*>(out)[out_base + idx] = src[off];
+        }
     }
 }
 
@@ -289,12 +337,13 @@ __global__ void __launch_bounds__(256) delta_kernel(const int32_t* __restrict__ 
 }
 
 template <int U, int TPR>
-hipError_t launch_split_cfg(const SplitArgs& a, bool fp16, int64_t T, hipStream_t st) {
+hipError_t launch_split_cfg(const SplitArgs& a, int fmt, int64_t T, hipStream_t st) {
     constexpr int BLOCK = TPR < 256 ? 256 : TPR;
     constexpr int RPB = BLOCK / TPR;
     dim3 grid((unsigned)((a.rows_pad + RPB - 1) / RPB), (unsigned)T);
-    if (fp16) hipLaunchKernelGGL((split_kernel<U, TPR, true>), grid, dim3(BLOCK), 0, st, a);
-    else hipLaunchKernelGGL((split_kernel<U, TPR, false>), grid, dim3(BLOCK), 0, st, a);
+    if (fmt == FMT_FP16) hipLaunchKernelGGL((split_kernel<U, TPR, FMT_FP16>), grid, dim3(BLOCK), 0, st, a);
+    else if (fmt == FMT_FP6) hipLaunchKernelGGL((split_kernel<U, TPR, FMT_FP6>), grid, dim3(BLOCK), 0, st, a);
+    else hipLaunchKernelGGL((split_kernel<U, TPR, FMT_FP8>), grid, dim3(BLOCK), 0, st, a);
     return hipGetLastError();
 }
 
@@ -312,15 +361,15 @@ hipError_t launch_split(const double* X, int64_t ldv, const Plan& pl, const Oper
     a.X = X; a.ldv = ldv; a.rows = op.rows; a.rows_pad = op.rows_pad; a.k = pl.k; a.kb = pl.kb; a.chunks = pl.chunks;
     a.s = pl.s; a.b = pl.b; a.slices = op.slices; a.exps = op.exps; a.flags = flags;
     a.vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0) && (ldv % 2 == 0) && (pl.kb % 2 == 0 || pl.T == 1);
-    const bool fp16 = pl.fmt == 1;
-    const int64_t octets = pl.chunks * (CHUNK_BYTES / pl.elem_bytes) / 8;      // per vector and block, padded
-    if (octets <= 64) return launch_split_cfg<1, 64>(a, fp16, pl.T, st);
-    if (octets <= 128) return launch_split_cfg<2, 64>(a, fp16, pl.T, st);
-    if (octets <= 256) return launch_split_cfg<4, 64>(a, fp16, pl.T, st);
-    if (octets <= 512) return launch_split_cfg<8, 64>(a, fp16, pl.T, st);
-    if (octets <= 1024) return launch_split_cfg<4, 256>(a, fp16, pl.T, st);
-    if (octets <= 2048) return launch_split_cfg<8, 256>(a, fp16, pl.T, st);
-    if (octets <= 4096) return launch_split_cfg<4, 1024>(a, fp16, pl.T, st);
+    const int fmt = pl.fmt;
+    const int64_t octets = pl.chunks * pl.epc / 8;                              // per vector and block, padded
+    if (octets <= 64) return launch_split_cfg<1, 64>(a, fmt, pl.T, st);
+    if (octets <= 128) return launch_split_cfg<2, 64>(a, fmt, pl.T, st);
+    if (octets <= 256) return launch_split_cfg<4, 64>(a, fmt, pl.T, st);
+    if (octets <= 512) return launch_split_cfg<8, 64>(a, fmt, pl.T, st);
+    if (octets <= 1024) return launch_split_cfg<4, 256>(a, fmt, pl.T, st);
+    if (octets <= 2048) return launch_split_cfg<8, 256>(a, fmt, pl.T, st);
+    if (octets <= 4096) return launch_split_cfg<4, 1024>(a, fmt, pl.T, st);
     return hipErrorInvalidValue;                                                // the planner rejects longer blocks
 }
 
@@ -334,10 +383,12 @@ hipError_t launch_deltas(const Plan& pl, const Operand& op, hipStream_t st) {
 hipError_t launch_export_slices(const Plan& pl, const Operand& op, void* out, hipStream_t st) {
     if (op.rows == 0 || pl.k == 0) return hipSuccess;
     dim3 grid(1024, (unsigned)pl.s, (unsigned)pl.T);
-    if (pl.fmt == 1)
-        hipLaunchKernelGGL((export_slices_kernel<true>), grid, dim3(256), 0, st, op.slices, op.rows, op.rows_pad, pl.k, pl.kb, pl.chunks, pl.s, out);
+    if (pl.fmt == FMT_FP16)
+        hipLaunchKernelGGL((export_slices_kernel<FMT_FP16>), grid, dim3(256), 0, st, op.slices, op.rows, op.rows_pad, pl.k, pl.kb, pl.chunks, pl.s, out);
+    else if (pl.fmt == FMT_FP6)
+        hipLaunchKernelGGL((export_slices_kernel<FMT_FP6>), grid, dim3(256), 0, st, op.slices, op.rows, op.rows_pad, pl.k, pl.kb, pl.chunks, pl.s, out);
     else
-        hipLaunchKernelGGL((export_slices_kernel<false>), grid, dim3(256), 0, st, op.slices, op.rows, op.rows_pad, pl.k, pl.kb, pl.chunks, pl.s, out);
+        hipLaunchKernelGGL((export_slices_kernel<FMT_FP8>), grid, dim3(256), 0, st, op.slices, op.rows, op.rows_pad, pl.k, pl.kb, pl.chunks, pl.s, out);
     return hipGetLastError();
 }
 

@@ -41,7 +41,7 @@ def _gpu_split(X_rows_np, is_B, fmt, s, k_block):
         ws = device.Workspace.for_problem(rows, 0, k, FMT[fmt], s, k_block)
     plan = oz.make_plan(k, fmt, k_block)
     T = plan.num_blocks
-    dt = torch.uint8 if fmt == "fp8" else torch.int16
+    dt = torch.int16 if fmt == "fp16" else torch.uint8
     slices = torch.zeros(s * rows * k, dtype=dt, device="cuda")
     exps = torch.zeros(T * s * rows, dtype=torch.int32, device="cuda")
     lib.ozaki_split(int(is_B), rows, k, Xd, ldx, FMT[fmt], s, k_block, slices, exps)
@@ -76,6 +76,12 @@ SPLIT_CASES = [
     ("fp16", 40, 64, 0, 5, 2.0),          # b = 9
     ("fp16", 33, 16, 0, 5, 1.0),          # b = 10
     ("fp16", 19, 700, 256, 5, 2.0),       # b = 8, three blocks
+    ("fp6", 256, 256, 0, 12, 0.5),
+    ("fp6", 300, 1000, 0, 9, 4.0),        # ragged rows and k
+    ("fp6", 77, 1000, 384, 7, 2.0),       # three blocks, last one short
+    ("fp6", 40, 8192, 0, 16, 4.0),
+    ("fp6", 9, 20000, 0, 5, 1.0),
+    ("fp6", 17, 3, 0, 4, 1.0),
 ]
 
 
@@ -110,6 +116,10 @@ PRODUCT_CASES = [
     ("fp8", 100, 600, 1000, 384, 5, 4.0),
     ("fp16", 260, 130, 1100, 512, 5, 1.0),
     ("fp16", 64, 64, 4096, 0, 4, 1.0),
+    ("fp6", 256, 256, 256, 0, 12, 0.5),
+    ("fp6", 300, 270, 520, 0, 6, 2.0),
+    ("fp6", 100, 600, 1000, 384, 5, 4.0),
+    ("fp6", 515, 260, 4096, 0, 3, 1.0),
 ]
 
 
@@ -142,6 +152,10 @@ DGEMM_CASES = [
     ("fp16", 512, 256, 2048, 1024, 8, 1.0),
     ("fp8", 513, 255, 2048, 0, 13, 1.0),
     ("fp8", 16, 16, 16, 0, 3, 1.0),
+    ("fp6", 256, 256, 256, 0, 12, 0.5),
+    ("fp6", 300, 270, 520, 0, 15, 4.0),
+    ("fp6", 100, 600, 1000, 384, 12, 2.0),
+    ("fp6", 513, 255, 2048, 0, 13, 1.0),
 ]
 
 
@@ -265,7 +279,7 @@ def test_edge_cases_and_error_paths():
     assert lib.ozaki_dgemm(m, n, k, Ad, m - 1, Bd, k, Cd, m, 0, 4, 0, 0, check=False) == -5
     assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k - 1, Cd, m, 0, 4, 0, 0, check=False) == -7
     assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m - 1, 0, 4, 0, 0, check=False) == -9
-    assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 2, 4, 0, 0, check=False) == -10
+    assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 3, 4, 0, 0, check=False) == -10
     assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 0, 4, 0, 2, check=False) == -13
     assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 0, 33, 0, 0, check=False) == lib.STATUS_INFEASIBLE
     # workspace too small
