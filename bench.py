@@ -28,7 +28,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_TFLOPS = {"fp8": 5000.0, "fp16": 2500.0}          # MI355X dense MFMA peaks
+PEAK_TFLOPS = {"fp8": 5000.0, "fp16": 2500.0, "fp6": 10100.0}          # MI355X dense MFMA peaks
+DTYPE_NAMES = {"fp8": "fp8_e4m3", "fp16": "fp16", "fp6": "fp6_e2m3"}
 DEFAULT_CONFIG = "c3_8192_fp8_emu"                      # the configuration the metric is quoted on (n = 8192)
 # L2-fill + write-back bytes of one pair_gemm_kernel launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script (scaled by the 1 GiB copy-calibration kernel); see profiles/ozaki_dgemm_c3_8192_fp8_emu.md.  Only valid for
@@ -44,6 +45,8 @@ def parse_args():
     ap.add_argument("--config", default=DEFAULT_CONFIG)
     ap.add_argument("--num-slices", type=int, default=0, help="0: the calibrated full-accuracy count of the configuration")
     ap.add_argument("--accum", choices=["hw", "emu"], default=None, help="override the configuration's accumulation mode")
+    ap.add_argument("--slice-format", choices=["fp8", "fp16", "fp6"], default=None,
+                    help="override the configuration's slice format (fp6 = E2M3: same slices and same C as fp8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sample", type=int, default=0, help="rows/columns of the CPU-oracle sample (0: sized for ~15 s)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -115,6 +118,8 @@ def main():
     cfg = dict(inputs.CONFIGS[args.config])
     if args.accum:
         cfg["accum"] = args.accum
+    if args.slice_format:
+        cfg["fmt"] = args.slice_format
     m, n, k, fmt, kb = cfg["m"], cfg["n"], cfg["k"], cfg["fmt"], cfg["k_block"]
     s = args.num_slices or inputs.NUM_SLICES[args.config]
     pairs = s * (s + 1) // 2
@@ -161,7 +166,7 @@ def main():
         "metric": "effective FP64 TFLOPS (2mnk/t) at n=8192; % FP8 MFMA peak; max rel err",
         "value": eff_tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec_per_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "fp8_e4m3" if fmt == "fp8" else "fp16", "data": "synthetic",
+        "dtype": DTYPE_NAMES[fmt], "data": "synthetic",
         "config": {
             "workload": f"{args.config}: m={m} n={n} k={k}, entries (U(0,1)-0.5)*exp({cfg['phi']}*N(0,1)) seed 0",
             "slice_format": fmt, "num_slices": s, "slice_pairs": pairs, "k_block": kb or k,
@@ -170,7 +175,7 @@ def main():
         "roofline": {
             "kernel": "pair_gemm_kernel", "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
             "frac": achieved / peak,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if not args.num_slices else None, "traffic_unit": "bytes per launch",
+            "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if not (args.num_slices or args.slice_format) else None, "traffic_unit": "bytes per launch",
             "avg_launch_ms": gemm_launch_ms, "launches_per_step": launches[1] / args.steps,
         },
         "phases_ms_per_step": {"slicing": phase_ms[0] / args.steps, "pair_gemms": phase_ms[1] / args.steps,

@@ -131,7 +131,7 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
         }
     };
     // Per element, consecutive stored runs of one group with the same scale are merged further (32-bit integer,
-    // units of 2^-two_b) before the FP64 addition: together with the tile-wide runs formed by the GEMM kernel this
+    // units of 2^-p_frac) before the FP64 addition: together with the tile-wide runs formed by the GEMM kernel this
     // is the element-wise rule "consecutive pairs of a group with equal scale are summed exactly".
     int run_sum[4] = {0, 0, 0, 0}, run_e[4] = {0, 0, 0, 0};
     auto process = [&](uint32_t entry, const uint4& v) {
@@ -142,7 +142,8 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int e = eA + (q == 0 ? 0 : relB[q][nl + r]);
-            const int iv = fp32_bits_to_scaled_int(vv[r], a.p_frac);
+            // the product as an integer in units of 2^-p_frac: exact in FP32 (|integer| <= 2^24), no FP64 involved
+            const int iv = (int)ldexpf(__uint_as_float(vv[r]), a.p_frac);
             if (!first && e == run_e[r]) {
                 run_sum[r] += iv;
             } else {

@@ -94,17 +94,6 @@ OZAKI_HD uint64_t fp32_bits_scaled_to_fp64(uint32_t f, int e2) {
     return sign | ((uint64_t)e << 52) | ((uint64_t)(f & 0x7FFFFFu) << 29);
 }
 
-// The integer n with f = n * 2^-frac_bits, for an FP32 bit pattern f that is such a multiple with |n| <= 2^24
-// (an exact slice-pair product).  Integer-only.
-OZAKI_HD int fp32_bits_to_scaled_int(uint32_t f, int frac_bits) {
-    if ((f << 1) == 0) return 0;
-    const int e = (int)((f >> 23) & 0xFF);                   // f = m * 2^(e-150), m = 24-bit significand
-    const uint32_t m = (f & 0x7FFFFFu) | 0x800000u;
-    const int sh = 150 - e - frac_bits;                      // 23 >= sh >= -1 (sh = -1 only for |n| = 2^24)
-    const int n = (int)(sh >= 0 ? (m >> sh) : (m << -sh));
-    return (f >> 31) ? -n : n;
-}
-
 // n * 2^e2 as FP64 bits for a 32-bit integer n (exact), integer-only; flushed / saturated outside the normal range.
 OZAKI_HD uint64_t int32_scaled_to_fp64(int n, int e2) {
     if (n == 0) return 0;
