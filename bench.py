@@ -34,7 +34,7 @@ DEFAULT_CONFIG = "c3_8192_fp8_emu"                      # the configuration the 
 # L2-fill + write-back bytes of one pair_gemm_kernel launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script (scaled by the 1 GiB copy-calibration kernel); see profiles/ozaki_dgemm_c3_8192_fp8_emu.md.  Only valid for
 # the configuration's calibrated slice count.
-MEASURED_TRAFFIC_BYTES = {"c3_8192_fp8_emu": 124.04 * 2 ** 30}
+MEASURED_TRAFFIC_BYTES = {("c3_8192_fp8_emu", "fp8"): 124.78 * 2 ** 30, ("c3_8192_fp8_emu", "fp6"): 91.13 * 2 ** 30}
 
 
 def parse_args():
@@ -68,7 +68,7 @@ def cpu_baseline_leg(cfg, s, A, B, Cd, sample):
     cols = np.sort(rng.choice(n, min(sample, n), replace=False))
     As, Bs = np.ascontiguousarray(A[rows, :]), np.ascontiguousarray(B[:, cols])
     t0 = time.perf_counter()
-    Cref = oz.ozaki_dgemm(As, Bs, cfg["fmt"], s, cfg["k_block"])
+    Cref = oz.ozaki_dgemm(As, Bs, cfg["fmt"], s, cfg["k_block"], mode="full" if cfg.get("pairs") == "all" else "triangle")
     t_cpu = time.perf_counter() - t0
     Csub = Cd[torch.from_numpy(cols).cuda()][:, torch.from_numpy(rows).cuda()].cpu().numpy().T
     bit_equal = bool(np.array_equal(Csub.view(np.uint64), Cref.view(np.uint64)))
@@ -115,23 +115,25 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
     lib.load()
-    cfg = dict(inputs.CONFIGS[args.config])
+    cfg = dict(inputs.CONFIGS.get(args.config) or inputs.PAPER_CONFIGS[args.config])
     if args.accum:
         cfg["accum"] = args.accum
     if args.slice_format:
         cfg["fmt"] = args.slice_format
     m, n, k, fmt, kb = cfg["m"], cfg["n"], cfg["k"], cfg["fmt"], cfg["k_block"]
-    s = args.num_slices or inputs.NUM_SLICES[args.config]
-    pairs = s * (s + 1) // 2
+    s = args.num_slices or inputs.NUM_SLICES.get(args.config) or inputs.PAPER_NUM_SLICES[args.config]
+    all_pairs = cfg.get("pairs") == "all"
+    pairs = s * s if all_pairs else s * (s + 1) // 2
+    s_arg = s | lib.PAIRS_ALL if all_pairs else s
     fmt_id, acc_id = lib.SLICE_FORMATS[fmt], lib.ACCUM_MODES[cfg["accum"]]
 
-    A, B = inputs.phi_pair(m, n, k, cfg["phi"], seed=0)
+    A, B = inputs.config_pair(cfg, seed=0)
     Ad, Bd = device.to_device_colmajor(A), device.to_device_colmajor(B)
     Cd = torch.empty((n, m), dtype=torch.float64, device="cuda")
-    ws = device.Workspace.for_problem(m, n, k, fmt_id, s, kb)
+    ws = device.Workspace.for_problem(m, n, k, fmt_id, s_arg, kb)
 
     def step():
-        lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, fmt_id, s, kb, acc_id)
+        lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, fmt_id, s_arg, kb, acc_id)
 
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
@@ -168,14 +170,15 @@ def main():
         "ms_per_step": sec_per_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": DTYPE_NAMES[fmt], "data": "synthetic",
         "config": {
-            "workload": f"{args.config}: m={m} n={n} k={k}, entries (U(0,1)-0.5)*exp({cfg['phi']}*N(0,1)) seed 0",
+            "workload": f"{args.config}: m={m} n={n} k={k}, entries "
+                        + ("U(1,10)" if cfg.get("dist") == "u110" else f"(U(0,1)-0.5)*exp({cfg['phi']}*N(0,1))") + " seed 0",
             "slice_format": fmt, "num_slices": s, "slice_pairs": pairs, "k_block": kb or k,
             "accum_mode": "integer-emulated FP64" if cfg["accum"] == "emu" else "hardware FP64",
         },
         "roofline": {
             "kernel": "pair_gemm_kernel", "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
             "frac": achieved / peak,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if not (args.num_slices or args.slice_format) else None, "traffic_unit": "bytes per launch",
+            "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, fmt)) if not args.num_slices else None, "traffic_unit": "bytes per launch",
             "avg_launch_ms": gemm_launch_ms, "launches_per_step": launches[1] / args.steps,
         },
         "phases_ms_per_step": {"slicing": phase_ms[0] / args.steps, "pair_gemms": phase_ms[1] / args.steps,

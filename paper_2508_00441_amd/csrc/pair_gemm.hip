@@ -61,7 +61,6 @@ struct GemmArgs {
     Pass pass;
 };
 
-constexpr int NSTAGE = 4;
 static_assert(CHUNK_BYTES == 64, "the swizzle and the fragment addressing below assume 64-byte LDS rows");
 
 #define OZAKI_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
@@ -87,6 +86,7 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
     constexpr int OPERAND_BYTES = TILE * BK;          // one operand's share of a stage
     constexpr int STAGE_BYTES = 2 * OPERAND_BYTES;    // X tile + Y tile
     constexpr int LPW = OPERAND_BYTES / 1024 / 4;     // direct-to-LDS load instructions per wave, operand and stage
+    constexpr int NSTAGE = FP6 ? 6 : 5;               // ring of stage buffers: 5 x 32 KiB resp. 6 x 24 KiB of the 160 KiB LDS
     constexpr int KS = FP16 ? 2 : 1;                  // MFMA k-steps per stage (32 resp. 64 inner indices each)
     constexpr int READS = FP16 ? 8 : 16;              // LDS read instructions per wave and k-step
     __shared__ __attribute__((aligned(16))) uint8_t lds[NSTAGE * STAGE_BYTES];

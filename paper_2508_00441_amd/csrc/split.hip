@@ -93,7 +93,12 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
     __shared__ int red[2][BLOCK / 64];
 
     const int tr = threadIdx.x % TPR;
-    const int64_t row = (int64_t)blockIdx.x * RPB + threadIdx.x / TPR;
+    // Workgroups are handed to the eight XCDs (each with an L2 of its own) round-robin by their index.  Neighbouring
+    // vectors share the cache lines of the slice layout (a line holds the 16-byte pieces of eight vectors in the
+    // FP6 planes, the 64-byte chunks of two vectors otherwise), so consecutive vectors go to workgroups of the SAME
+    // XCD, where the partial lines meet in one L2 before they are written back.  gridDim.x is a multiple of 8.
+    const int64_t wg = (int64_t)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int64_t row = wg * RPB + threadIdx.x / TPR;
     const int64_t t = blockIdx.y;
     const int64_t k0 = t * a.kb;
     int64_t klen = a.k - k0;

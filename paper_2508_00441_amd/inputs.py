@@ -58,6 +58,27 @@ CONFIGS = {
     "c5b_1024x65536_fp8":   dict(m=1024,  n=1024,  k=65536, phi=2.0, fmt="fp8",  k_block=8192, accum="emu"),
 }
 
+#: The paper's own workload (Section 5.1): square matrices with entries uniform in (1, 10), every one of the s^2 slice
+#: pairs multiplied, s = the slice count behind Table 2 for the block length (11 for FP8; 7 for FP16 with 1024-element
+#: blocks), which brings the result to the correctly rounded product on the calibration sample.
+PAPER_CONFIGS = {}
+PAPER_NUM_SLICES = {}
+for _n in (1024, 2048, 4096, 8192, 16384):
+    PAPER_CONFIGS[f"paper_u110_n{_n}_fp8"] = dict(m=_n, n=_n, k=_n, dist="u110", fmt="fp8", k_block=0, accum="hw", pairs="all")
+    PAPER_NUM_SLICES[f"paper_u110_n{_n}_fp8"] = 11
+    PAPER_CONFIGS[f"paper_u110_n{_n}_fp16_kb1024"] = dict(m=_n, n=_n, k=_n, dist="u110", fmt="fp16", k_block=1024, accum="hw",
+                                                          pairs="all")
+    PAPER_NUM_SLICES[f"paper_u110_n{_n}_fp16_kb1024"] = 7
+
+
+def config_pair(cfg: dict, seed: int = 0):
+    """A (m x k) and B (k x n) of a configuration: the phi recipe, or uniform (1, 10) where it says dist="u110"."""
+    if cfg.get("dist", "phi") == "u110":
+        rng = np.random.default_rng(seed)
+        return uniform_1_10(cfg["m"], cfg["k"], rng), uniform_1_10(cfg["k"], cfg["n"], rng)
+    return phi_pair(cfg["m"], cfg["n"], cfg["k"], cfg["phi"], seed=seed)
+
+
 #: Slices per configuration for full FP64 accuracy (error no larger than a plain FP64 GEMM on the same
 #: entries): the s_native column of tests/golden/slices_per_config.txt.  S_BOUND is the smallest count
 #: that meets the componentwise bound 4 k 2^-53.

@@ -15,3 +15,20 @@ def test_num_slices_table_matches_calibration_file(golden_dir):
     assert set(seen) == set(inputs.CONFIGS) == set(inputs.NUM_SLICES) == set(inputs.S_BOUND)
     for name, (sb, sn) in seen.items():
         assert inputs.S_BOUND[name] == sb and inputs.NUM_SLICES[name] == sn, name
+
+
+def test_paper_workload_uses_the_slice_counts_of_table_2(golden_dir):
+    """Section 5.1 workload: U(1,10) square matrices, all s^2 pairs, s^2 = the Table 2 entry for the block length."""
+    table = {}
+    with open(os.path.join(golden_dir, "table2_min_gemms.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            parts = line.split()
+            table[int(parts[0])] = parts[1:]
+    for name, cfg in inputs.PAPER_CONFIGS.items():
+        s = inputs.PAPER_NUM_SLICES[name]
+        kb = cfg["k_block"] or cfg["k"]
+        col = 0 if cfg["fmt"] == "fp16" else 2                  # FP16 / FP8 E4M3 with FP32 accumulation
+        assert s * s == int(table[kb][col]), name
+        assert cfg["pairs"] == "all" and cfg["dist"] == "u110" and cfg["m"] == cfg["n"] == cfg["k"]
