@@ -368,12 +368,14 @@ hipError_t launch_split(const double* X, int64_t ldv, const Plan& pl, const Oper
     a.vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0) && (ldv % 2 == 0) && (pl.kb % 2 == 0 || pl.T == 1);
     const int fmt = pl.fmt;
     const int64_t octets = pl.chunks * pl.epc / 8;                              // per vector and block, padded
+    // sixteen elements per thread (U = 2) is the measured optimum: more elements per thread cost registers and with
+    // them the occupancy that hides the latency of the dependent integer chains (64 per thread: one wave per SIMD)
     if (octets <= 64) return launch_split_cfg<1, 64>(a, fmt, pl.T, st);
     if (octets <= 128) return launch_split_cfg<2, 64>(a, fmt, pl.T, st);
-    if (octets <= 256) return launch_split_cfg<4, 64>(a, fmt, pl.T, st);
-    if (octets <= 512) return launch_split_cfg<8, 64>(a, fmt, pl.T, st);
-    if (octets <= 1024) return launch_split_cfg<4, 256>(a, fmt, pl.T, st);
-    if (octets <= 2048) return launch_split_cfg<8, 256>(a, fmt, pl.T, st);
+    if (octets <= 256) return launch_split_cfg<2, 128>(a, fmt, pl.T, st);
+    if (octets <= 512) return launch_split_cfg<2, 256>(a, fmt, pl.T, st);
+    if (octets <= 1024) return launch_split_cfg<2, 512>(a, fmt, pl.T, st);
+    if (octets <= 2048) return launch_split_cfg<2, 1024>(a, fmt, pl.T, st);
     if (octets <= 4096) return launch_split_cfg<4, 1024>(a, fmt, pl.T, st);
     return hipErrorInvalidValue;                                                // the planner rejects longer blocks
 }
