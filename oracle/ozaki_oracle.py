@@ -259,26 +259,41 @@ def block_result(Ab: np.ndarray, Bb: np.ndarray, plan: Plan, num_slices: int, mo
     return BlockResult(sa, sb, ca, cb, pairs, products, S)
 
 
+def hw_mul(x, y):
+    """FP64 multiplication of the host (IEEE, round to nearest even)."""
+    return np.multiply(x, y, dtype=np.float64)
+
+
 def ozaki_dgemm(A: np.ndarray, B: np.ndarray, fmt: str = "fp8", num_slices: int = 11, k_block: int = 0,
-                mode: str = "triangle", add: Callable = hw_add, return_blocks: bool = False, group: bool = True):
+                mode: str = "triangle", add: Callable = hw_add, return_blocks: bool = False, group: bool = True,
+                alpha: float = 1.0, beta: float = 0.0, C0: np.ndarray = None, mul: Callable = hw_mul):
     """C = A B by the Ozaki scheme with inner-product-wise blocking (Section 4.3): every block's sum is
-    formed first, then added to C in FP64, blocks in ascending k."""
+    formed first, then added to C in FP64, blocks in ascending k.
+
+    With alpha / beta (the GEMM of the BLAS the paper emulates, Section 1; the scaling needs the FP64
+    multiplication that Section 4.2 emulates next to the addition) the product P formed as above is combined as
+        C = fl(fl(alpha * P) + fl(beta * C0)),   beta == 0: C = fl(alpha * P) and C0 is not read,
+        alpha == 1 and beta == 0: C = P (no arithmetic),
+    one rounded multiplication per term and one rounded addition, no fused multiply-add."""
     A = np.asarray(A, dtype=np.float64)
     B = np.asarray(B, dtype=np.float64)
     m, k = A.shape
     k2, n = B.shape
     assert k == k2
     C = np.zeros((m, n), dtype=np.float64)
-    if k == 0:
-        return (C, []) if return_blocks else C
-    plan = make_plan(k, fmt, k_block)
     blocks = []
-    for t in range(plan.num_blocks):
-        k0, k1 = t * plan.k_block, min(k, (t + 1) * plan.k_block)
-        br = block_result(A[:, k0:k1], B[k0:k1, :], plan, num_slices, mode, add, keep=return_blocks, group=group)
-        C = add(C, br.S)
-        if return_blocks:
-            blocks.append(br)
+    if k > 0:
+        plan = make_plan(k, fmt, k_block)
+        for t in range(plan.num_blocks):
+            k0, k1 = t * plan.k_block, min(k, (t + 1) * plan.k_block)
+            br = block_result(A[:, k0:k1], B[k0:k1, :], plan, num_slices, mode, add, keep=return_blocks, group=group)
+            C = add(C, br.S)
+            if return_blocks:
+                blocks.append(br)
+    if not (alpha == 1.0 and beta == 0.0):
+        C = mul(np.float64(alpha), C)
+        if beta != 0.0:
+            C = add(C, mul(np.float64(beta), np.asarray(C0, dtype=np.float64)))
     return (C, blocks) if return_blocks else C
 
 

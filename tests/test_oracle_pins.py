@@ -453,6 +453,59 @@ def test_emulated_accumulation_gives_the_same_bits():
         assert np.array_equal(C_hw.view(np.uint64), C_sw.view(np.uint64))
 
 
+def test_soft_mul_is_bitwise_the_host_fpu():
+    """Section 4.2: the integer-only multiplication equals the hardware one bit for bit (normal range)."""
+    rng = np.random.default_rng(23)
+    n = 2_000_000
+
+    def rnd(cnt, lo, hi):
+        frac = rng.integers(0, 1 << 52, cnt, dtype=np.uint64)
+        e = rng.integers(lo + 1023, hi + 1023, cnt, dtype=np.uint64)
+        sg = rng.integers(0, 2, cnt, dtype=np.uint64)
+        return ((sg << np.uint64(63)) | (e << np.uint64(52)) | frac).view(np.float64)
+
+    a = rnd(5 * n, -300, 300)
+    b = rnd(5 * n, -300, 300)
+    # products that are exactly representable or exact ties: few significant bits in both factors
+    a[n:2 * n] = np.ldexp(rng.integers(1, 1 << 27, n).astype(np.float64), rng.integers(-200, 200, n))
+    b[n:2 * n] = np.ldexp(rng.integers(1, 1 << 27, n).astype(np.float64), rng.integers(-200, 200, n))
+    # significands whose product lands next to a power of two (rounding carries into the next binade)
+    a[2 * n:3 * n] = np.nextafter(2.0, 0.0) * np.ldexp(1.0, rng.integers(-100, 100, n))
+    b[2 * n:3 * n] = (1.0 + np.ldexp(rng.integers(0, 8, n).astype(np.float64), -52)) * np.ldexp(1.0, rng.integers(-100, 100, n))
+    a[:4] = [0.0, -0.0, 3.0, -1.5]
+    b[:4] = [5.0, 2.0, 0.0, -0.0]
+    got = softfloat.soft_mul(a, b)
+    assert np.array_equal(got.view(np.uint64), (a * b).view(np.uint64))
+    # the bit-level entry point and one value worked by hand: (1 + 2^-52)^2 = 1 + 2^-51 + 2^-104 -> 1 + 2^-51
+    x = np.nextafter(1.0, 2.0)
+    assert softfloat.soft_mul_bits(int(np.float64(x).view(np.uint64)), int(np.float64(x).view(np.uint64))) == int(np.float64(1.0 + 2.0 ** -51).view(np.uint64))
+
+
+def test_alpha_beta_combination_follows_its_definition():
+    """C = fl(fl(alpha P) + fl(beta C0)) around the product P of the plain call; emulated arithmetic gives the same bits."""
+    rng = np.random.default_rng(31)
+    A = inputs.phi_matrix(20, 96, 1.0, rng)
+    B = inputs.phi_matrix(96, 24, 1.0, rng)
+    C0 = inputs.phi_matrix(20, 24, 2.0, rng)
+    P = oz.ozaki_dgemm(A, B, "fp8", 9, 32)
+    for alpha, beta in ((1.0, 0.0), (-2.5, 0.0), (1.0, 1.0), (0.3, -1.7), (0.0, 2.0)):
+        C = oz.ozaki_dgemm(A, B, "fp8", 9, 32, alpha=alpha, beta=beta, C0=C0)
+        want = P if (alpha, beta) == (1.0, 0.0) else (alpha * P if beta == 0.0 else alpha * P + beta * C0)
+        assert np.array_equal(C.view(np.uint64), want.view(np.uint64)), (alpha, beta)
+        Csw = oz.ozaki_dgemm(A, B, "fp8", 9, 32, alpha=alpha, beta=beta, C0=C0, add=softfloat.soft_add, mul=softfloat.soft_mul)
+        assert np.array_equal(C.view(np.uint64), Csw.view(np.uint64)), (alpha, beta)
+    # beta == 0 does not read C0 (BLAS convention): NaNs there do not propagate
+    Cn = oz.ozaki_dgemm(A, B, "fp8", 9, 32, alpha=2.0, beta=0.0, C0=np.full((20, 24), np.nan))
+    assert np.array_equal(Cn, 2.0 * P)
+    # against the exact product: alpha * (A B) + beta * C0 within the GEMM bound plus the three extra roundings
+    ent = exact.sample_entries(20, 24, 12, seed=3)
+    C = oz.ozaki_dgemm(A, B, "fp8", 11, 32, alpha=0.3, beta=-1.7, C0=C0)
+    for i, j in ent:
+        ex = Fraction(0.3) * exact.exact_dot(A[i, :], B[:, j]) + Fraction(-1.7) * Fraction(float(C0[i, j]))
+        scale = abs(0.3) * float(np.abs(A[i, :]) @ np.abs(B[:, j])) + 1.7 * abs(float(C0[i, j]))
+        assert abs(Fraction(float(C[i, j])) - ex) <= Fraction(4 * 96 * 2.0 ** -53 + 3 * 2.0 ** -53) * Fraction(scale)
+
+
 def test_exact_reference_is_exact():
     # closed form: sum_{i<=N} i*(N+1-i) = N(N+1)(N+2)/6, with a huge cancelling pair on top
     N = 500
