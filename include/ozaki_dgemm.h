@@ -105,6 +105,26 @@ int ozaki_dgemm(int64_t m, int64_t n, int64_t k,
                 double* C, int64_t ldc,
                 int slice_format, int num_slices, int64_t k_block, int accum_mode);
 
+/*
+ * ozaki_dgemm_scaled -- C := alpha (A B) + beta C, the GEMM of the BLAS that the paper emulates (Section 1), with
+ * the FP64 multiplication of Section 4.2 beside the addition.
+ *   alpha, beta   HOST values; zeros or normal numbers.
+ *   The product P = A B is formed exactly as by ozaki_dgemm (same arguments, same bits), then every entry is
+ *   combined as  C = fl(fl(alpha * P) + fl(beta * C))  -- one rounded multiplication per term and one rounded
+ *   addition, no fused multiply-add; with beta == 0, C = fl(alpha * P) and the old C is not read (it may hold
+ *   anything); with alpha == 1 and beta == 0 the call is ozaki_dgemm.  In OZAKI_ACCUM_FP64_INT_EMU mode the
+ *   multiplications and the addition are integer-only too (same bits; the old C must then hold zeros or
+ *   normal numbers).  All other arguments as for ozaki_dgemm.
+ *   The workspace must have ozaki_workspace_bytes_scaled bytes (ozaki_workspace_bytes plus the m x n product),
+ *   or at least ozaki_workspace_min_bytes plus 8 m n rounded up to 256.
+ * Returns as ozaki_dgemm; negative values count positions in THIS argument list.
+ */
+int ozaki_dgemm_scaled(int64_t m, int64_t n, int64_t k, double alpha,
+                       const double* A, int64_t lda, const double* B, int64_t ldb,
+                       double beta, double* C, int64_t ldc,
+                       int slice_format, int num_slices, int64_t k_block, int accum_mode);
+size_t ozaki_workspace_bytes_scaled(int64_t m, int64_t n, int64_t k, int slice_format, int num_slices, int64_t k_block);
+
 /* Stream (a hipStream_t passed as void*; NULL = the null stream) used by all later calls. HOST call. */
 int ozaki_set_stream(void* hip_stream);
 

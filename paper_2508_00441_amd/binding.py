@@ -32,6 +32,9 @@ _i64, _int, _vp, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_s
 SIGNATURES = {
     "ozaki_plan": (_int, [_i64, _int, ctypes.POINTER(_int), ctypes.POINTER(_int)]),
     "ozaki_dgemm": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int, _int, _i64, _int]),
+    "ozaki_dgemm_scaled": (_int, [_i64, _i64, _i64, ctypes.c_double, _vp, _i64, _vp, _i64, ctypes.c_double, _vp, _i64, _int, _int,
+                                  _i64, _int]),
+    "ozaki_workspace_bytes_scaled": (_sz, [_i64, _i64, _i64, _int, _int, _i64]),
     "ozaki_set_stream": (_int, [_vp]),
     "ozaki_workspace_bytes": (_sz, [_i64, _i64, _i64, _int, _int, _i64]),
     "ozaki_workspace_min_bytes": (_sz, [_i64, _i64, _i64, _int, _int, _i64]),
@@ -103,6 +106,10 @@ def ozaki_workspace_bytes(m, n, k, slice_format, num_slices, k_block) -> int:
     return int(load().ozaki_workspace_bytes(m, n, k, slice_format, num_slices, k_block))
 
 
+def ozaki_workspace_bytes_scaled(m, n, k, slice_format, num_slices, k_block) -> int:
+    return int(load().ozaki_workspace_bytes_scaled(m, n, k, slice_format, num_slices, k_block))
+
+
 def ozaki_workspace_min_bytes(m, n, k, slice_format, num_slices, k_block) -> int:
     return int(load().ozaki_workspace_min_bytes(m, n, k, slice_format, num_slices, k_block))
 
@@ -134,6 +141,13 @@ def ozaki_profile_read():
 def ozaki_dgemm(m, n, k, A, lda, B, ldb, C, ldc, slice_format, num_slices, k_block, accum_mode, check: bool = True) -> int:
     st = load().ozaki_dgemm(m, n, k, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, slice_format, num_slices, k_block, accum_mode)
     return _check(st, "ozaki_dgemm") if check else st
+
+
+def ozaki_dgemm_scaled(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, slice_format, num_slices, k_block, accum_mode,
+                       check: bool = True) -> int:
+    st = load().ozaki_dgemm_scaled(m, n, k, float(alpha), _ptr(A), lda, _ptr(B), ldb, float(beta), _ptr(C), ldc, slice_format,
+                                   num_slices, k_block, accum_mode)
+    return _check(st, "ozaki_dgemm_scaled") if check else st
 
 
 def ozaki_split(is_B, rows, k, X, ldx, slice_format, num_slices, k_block, slices_out, exps_out, check: bool = True) -> int:

@@ -218,6 +218,28 @@ __global__ void __launch_bounds__(256) add_emulated_kernel(const uint64_t* a, co
         out[i] = fp64_add_emulated(a[i], b[i]);
 }
 
+// C = fl(fl(alpha * W) + fl(beta * C)), or C = fl(alpha * W) without reading C when use_beta == 0: the scaling
+// around the product, with the FP64 multiplication and addition in hardware or emulated (Section 4.2).
+template <bool EMU>
+__global__ void __launch_bounds__(256) axpby_kernel(uint64_t alpha, uint64_t beta, int use_beta, const uint64_t* __restrict__ W,
+                                                    int64_t ldw, uint64_t* C, int64_t ldc, int64_t m, int64_t n) {
+    const int64_t total = m * n;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+        const int64_t i = idx % m, j = idx / m;
+        const uint64_t w = W[i + j * ldw];
+        uint64_t* dst = C + i + j * ldc;
+        if constexpr (EMU) {
+            uint64_t t = fp64_mul_emulated(alpha, w);
+            if (use_beta) t = fp64_add_emulated(t, fp64_mul_emulated(beta, *dst));
+            *dst = t;
+        } else {
+            double t = __dmul_rn(__longlong_as_double((long long)alpha), __longlong_as_double((long long)w));
+            if (use_beta) t = __dadd_rn(t, __dmul_rn(__longlong_as_double((long long)beta), __longlong_as_double((long long)*dst)));
+            *dst = (uint64_t)__double_as_longlong(t);
+        }
+    }
+}
+
 __global__ void __launch_bounds__(256) fill_zero_kernel(uint64_t* C, int64_t ldc, int64_t m, int64_t n) {
     const int64_t total = m * n;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256)
@@ -271,6 +293,22 @@ hipError_t launch_add_emulated(const double* a, const double* b, double* out, in
     if (n <= 0) return hipSuccess;
     hipLaunchKernelGGL(add_emulated_kernel, dim3(grid_for(n)), dim3(256), 0, st, reinterpret_cast<const uint64_t*>(a),
                        reinterpret_cast<const uint64_t*>(b), reinterpret_cast<uint64_t*>(out), n);
+    return hipGetLastError();
+}
+
+hipError_t launch_axpby(double alpha, double beta, const double* W, int64_t ldw, double* C, int64_t ldc, int64_t m, int64_t n,
+                        int accum_mode, hipStream_t st) {
+    if (m <= 0 || n <= 0) return hipSuccess;
+    uint64_t ab, bb;
+    memcpy(&ab, &alpha, 8);
+    memcpy(&bb, &beta, 8);
+    const int use_beta = beta != 0.0;
+    if (accum_mode == 1)
+        hipLaunchKernelGGL((axpby_kernel<true>), dim3(grid_for(m * n)), dim3(256), 0, st, ab, bb, use_beta,
+                           reinterpret_cast<const uint64_t*>(W), ldw, reinterpret_cast<uint64_t*>(C), ldc, m, n);
+    else
+        hipLaunchKernelGGL((axpby_kernel<false>), dim3(grid_for(m * n)), dim3(256), 0, st, ab, bb, use_beta,
+                           reinterpret_cast<const uint64_t*>(W), ldw, reinterpret_cast<uint64_t*>(C), ldc, m, n);
     return hipGetLastError();
 }
 

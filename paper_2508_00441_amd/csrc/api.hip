@@ -83,6 +83,7 @@ struct Carve {
     int* flags;
     double* At;
     Operand A, B;
+    double* W;            // m x n product buffer of the scaled call (null otherwise)
     double* S;
     float* P;
     int chunk_pairs;
@@ -112,8 +113,10 @@ size_t minimum_bytes(const Plan& pl) {
     return fixed_bytes(pl) + sum_bytes(pl) + (size_t)pl.s * pair_bytes(pl);
 }
 
+size_t product_bytes(const Plan& pl) { return align_up((size_t)pl.m * pl.n * sizeof(double)); }
+
 // Places every buffer in the workspace; returns false if it does not fit.
-bool carve(const Plan& pl, Carve& c) {
+bool carve(const Plan& pl, Carve& c, bool want_product = false) {
     if (!g.ws) return false;
     size_t off = 0;
     c.flags = reinterpret_cast<int*>(g.ws);
@@ -128,6 +131,8 @@ bool carve(const Plan& pl, Carve& c) {
     c.B.exps = reinterpret_cast<int32_t*>(g.ws + off); off += exps_bytes(pl, pl.n_pad);
     c.A.deltas = reinterpret_cast<int32_t*>(g.ws + off); off += deltas_bytes(pl, pl.m_pad);
     c.B.deltas = reinterpret_cast<int32_t*>(g.ws + off); off += deltas_bytes(pl, pl.n_pad);
+    c.W = nullptr;
+    if (want_product) { c.W = reinterpret_cast<double*>(g.ws + off); off += product_bytes(pl); }
     if (off > g.ws_bytes) return false;
     const size_t rest = g.ws_bytes - off, pb = pair_bytes(pl);
     if (pb == 0) { c.S = nullptr; c.P = nullptr; c.chunk_pairs = pl.npairs; return true; }
@@ -194,6 +199,66 @@ int run_split(const Plan& pl, const Carve& c, const double* A, int64_t lda, cons
     if (do_b && pl.n > 0) {
         HIP_TRY(launch_split(B, ldb, pl, c.B, c.flags, g.stream));
         HIP_TRY(launch_deltas(pl, c.B, g.stream));
+    }
+    return 0;
+}
+
+// zeros and normal numbers only: what the emulated multiplication covers (Section 4.2)
+bool scalar_ok(double v) {
+    uint64_t b;
+    memcpy(&b, &v, 8);
+    const int e = (int)((b >> 52) & 0x7FF);
+    return (e != 0 && e != 0x7FF) || (b << 1) == 0;
+}
+
+// C = alpha * (A B) + beta * C.  (alpha, beta) = (1, 0): the product goes straight to C.  Otherwise it goes to the
+// workspace's product buffer and one more kernel combines it with C.  Error codes: argument positions of ozaki_dgemm.
+int dgemm_core(int64_t m, int64_t n, int64_t k, double alpha, const double* A, int64_t lda, const double* B, int64_t ldb,
+               double beta, double* C, int64_t ldc, int slice_format, int num_slices, int64_t k_block, int accum_mode) {
+    Plan pl;
+    const int st = make_plan(m, n, k, slice_format, num_slices & ~OZAKI_PAIRS_ALL, k_block, (num_slices & OZAKI_PAIRS_ALL) != 0, pl);
+    if (st != 0) return st;
+    if (accum_mode != OZAKI_ACCUM_FP64_HW && accum_mode != OZAKI_ACCUM_FP64_INT_EMU) return -13;
+    if (m == 0 || n == 0) return 0;
+    if (!C) return -8;
+    if (ldc < (m > 1 ? m : 1)) return -9;
+    const bool scaled = !(alpha == 1.0 && beta == 0.0);
+    if (k > 0) {
+        if (!A) return -4;
+        if (lda < (m > 1 ? m : 1)) return -5;
+        if (!B) return -6;
+        if (ldb < (k > 1 ? k : 1)) return -7;
+    }
+    Carve c;
+    c.W = nullptr;
+    if ((k > 0 || scaled) && !carve(pl, c, scaled)) return OZAKI_STATUS_WORKSPACE;
+    double* const out = scaled ? c.W : C;
+    const int64_t ldo = scaled ? (m > 1 ? m : 1) : ldc;
+    if (k == 0) {
+        HIP_TRY(launch_fill_zero_f64(out, ldo, m, n, g.stream));
+    } else {
+        const PairOrder order = order_of(pl);
+        int rc = run_split(pl, c, A, lda, B, ldb, true, true);
+        if (rc) return rc;
+        for (int64_t t = 0; t < pl.T; ++t) {
+            for (int g_hi = order_top_diag(order); g_hi >= 2;) {
+                const Pass ps = next_pass(order, g_hi, c.chunk_pairs);
+                {
+                    Phase ph(1);
+                    HIP_TRY(launch_pair_gemm(pl, c.A, c.B, order, ps, true, t, c.P, g.stream));
+                }
+                {
+                    Phase ph(2);
+                    HIP_TRY(launch_accumulate(pl, c.A, c.B, order, ps, g_hi == order_top_diag(order), ps.g_lo == 2, t, c.P, c.S, out,
+                                              ldo, accum_mode, g.stream));
+                }
+                g_hi = ps.g_lo - 1;
+            }
+        }
+    }
+    if (scaled) {
+        Phase ph(2);
+        HIP_TRY(launch_axpby(alpha, beta, c.W, ldo, C, ldc, m, n, accum_mode, g.stream));
     }
     return 0;
 }
@@ -287,43 +352,23 @@ int ozaki_profile_read(float* ms_out, int* launches_out) {
 
 int ozaki_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb,
                 double* C, int64_t ldc, int slice_format, int num_slices, int64_t k_block, int accum_mode) {
-    Plan pl;
-    const int st = make_plan(m, n, k, slice_format, num_slices & ~OZAKI_PAIRS_ALL, k_block, (num_slices & OZAKI_PAIRS_ALL) != 0, pl);
-    if (st != 0) return st;
-    if (accum_mode != OZAKI_ACCUM_FP64_HW && accum_mode != OZAKI_ACCUM_FP64_INT_EMU) return -13;
-    if (m == 0 || n == 0) return 0;
-    if (!C) return -8;
-    if (ldc < (m > 1 ? m : 1)) return -9;
-    if (k == 0) {
-        HIP_TRY(launch_fill_zero_f64(C, ldc, m, n, g.stream));
-        return 0;
-    }
-    if (!A) return -4;
-    if (lda < (m > 1 ? m : 1)) return -5;
-    if (!B) return -6;
-    if (ldb < (k > 1 ? k : 1)) return -7;
-    Carve c;
-    if (!carve(pl, c)) return OZAKI_STATUS_WORKSPACE;
-    const PairOrder order = order_of(pl);
+    return dgemm_core(m, n, k, 1.0, A, lda, B, ldb, 0.0, C, ldc, slice_format, num_slices, k_block, accum_mode);
+}
 
-    int rc = run_split(pl, c, A, lda, B, ldb, true, true);
-    if (rc) return rc;
-    for (int64_t t = 0; t < pl.T; ++t) {
-        for (int g_hi = order_top_diag(order); g_hi >= 2;) {
-            const Pass ps = next_pass(order, g_hi, c.chunk_pairs);
-            {
-                Phase ph(1);
-                HIP_TRY(launch_pair_gemm(pl, c.A, c.B, order, ps, true, t, c.P, g.stream));
-            }
-            {
-                Phase ph(2);
-                HIP_TRY(launch_accumulate(pl, c.A, c.B, order, ps, g_hi == order_top_diag(order), ps.g_lo == 2, t, c.P, c.S, C, ldc,
-                                          accum_mode, g.stream));
-            }
-            g_hi = ps.g_lo - 1;
-        }
-    }
-    return 0;
+int ozaki_dgemm_scaled(int64_t m, int64_t n, int64_t k, double alpha, const double* A, int64_t lda, const double* B, int64_t ldb,
+                       double beta, double* C, int64_t ldc, int slice_format, int num_slices, int64_t k_block, int accum_mode) {
+    if (!scalar_ok(alpha)) return -4;
+    if (!scalar_ok(beta)) return -9;
+    const int st = dgemm_core(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, slice_format, num_slices, k_block, accum_mode);
+    // argument positions of ozaki_dgemm -> positions in this signature (alpha and beta inserted)
+    if (st < 0) return st >= -3 ? st : st >= -7 ? st - 1 : st - 2;
+    return st;
+}
+
+size_t ozaki_workspace_bytes_scaled(int64_t m, int64_t n, int64_t k, int slice_format, int num_slices, int64_t k_block) {
+    Plan pl;
+    if (make_plan(m, n, k, slice_format, num_slices & ~OZAKI_PAIRS_ALL, k_block, (num_slices & OZAKI_PAIRS_ALL) != 0, pl) != 0) return 0;
+    return recommended_bytes(pl) + product_bytes(pl);
 }
 
 int ozaki_split(int is_B, int64_t rows, int64_t k, const double* X, int64_t ldx, int slice_format, int num_slices,

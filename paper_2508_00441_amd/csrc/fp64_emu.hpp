@@ -1,4 +1,4 @@
-// IEEE binary64 addition with 32/64-bit integer instructions only (paper Section 4.2).
+// IEEE binary64 addition and multiplication with 32/64-bit integer instructions only (paper Section 4.2).
 //
 // Round-to-nearest-even, bitwise equal to a hardware FP64 add for operands and results that are
 // zeros or normal numbers.  As in the paper, overflow, underflow and subnormal numbers are not
@@ -78,6 +78,42 @@ OZAKI_HD uint64_t fp64_add_emulated(uint64_t a, uint64_t b) {
     sig += (grs > 4u) | ((grs == 4u) & (unsigned)(sig & 1));   // ties to even; a carry to 2^53 is absorbed below
     if (e <= 0) return sign;
     uint64_t r = ((uint64_t)e << 52) + (sig - F64_HIDDEN);     // sig == 2^53 bumps the exponent, fraction 0
+    if (r >= F64_INF) return sign | F64_INF;
+    return sign | r;
+}
+
+// Full 64 x 64 -> 128 bit product from four 32 x 32 -> 64 bit partial products (the pen-and-paper scheme with
+// 32-bit digits of Section 4.2).  The middle column is summed in a way that cannot overflow: three terms below 2^32.
+OZAKI_HD void mul_64x64_128(uint64_t x, uint64_t y, uint64_t& hi, uint64_t& lo) {
+    const uint64_t x0 = (uint32_t)x, x1 = x >> 32, y0 = (uint32_t)y, y1 = y >> 32;
+    const uint64_t p00 = x0 * y0, p01 = x0 * y1, p10 = x1 * y0, p11 = x1 * y1;
+    const uint64_t mid = (p00 >> 32) + (uint32_t)p01 + (uint32_t)p10;
+    lo = (mid << 32) | (uint32_t)p00;
+    hi = p11 + (p01 >> 32) + (p10 >> 32) + (mid >> 32);
+}
+
+// a (x) b on raw bit patterns: IEEE binary64 multiplication, round-to-nearest-even, for zeros and normal numbers
+// (same contract as the addition above).
+OZAKI_HD uint64_t fp64_mul_emulated(uint64_t a, uint64_t b) {
+    const uint64_t sign = (a ^ b) & F64_SIGN;
+    const int ea = (int)((a >> 52) & 0x7FF), eb = (int)((b >> 52) & 0x7FF);
+    if (ea == 0 || eb == 0) return sign;
+    // significands scaled by 2^5 and 2^6: the 106-bit product scaled by 2^11 has its leading bit at position 116 or
+    // 115, so the upper word holds 53 or 52 significant bits and the lower word all the bits below them
+    const uint64_t ma = ((a & F64_FRAC) | F64_HIDDEN) << 5, mb = ((b & F64_FRAC) | F64_HIDDEN) << 6;
+    uint64_t hi, lo;
+    mul_64x64_128(ma, mb, hi, lo);
+    int e = ea + eb - 1023;
+    if (hi >> 52) {
+        e += 1;                                                // product of the significands in [2, 4)
+    } else {
+        hi = (hi << 1) | (lo >> 63);                           // in [1, 2): one more bit from below
+        lo <<= 1;
+    }
+    const uint64_t half = 0x8000000000000000ull;
+    hi += (uint64_t)((lo > half) | ((lo == half) & (unsigned)(hi & 1)));     // ties to even
+    if (e <= 0) return sign;
+    const uint64_t r = ((uint64_t)e << 52) + (hi - F64_HIDDEN);               // hi == 2^53 bumps the exponent
     if (r >= F64_INF) return sign | F64_INF;
     return sign | r;
 }

@@ -163,6 +163,11 @@ hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B,
 // P in accumulator order -> [nz][n][m] column-major matrices (verification export).
 hipError_t launch_export_products(const Plan& pl, int nz, const float* P, float* out, hipStream_t st);
 
+// C = alpha * W + beta * C element by element (one rounding per operation, no fused multiply-add; beta == 0: C is not
+// read), W and C column-major m x n.
+hipError_t launch_axpby(double alpha, double beta, const double* W, int64_t ldw, double* C, int64_t ldc, int64_t m, int64_t n,
+                        int accum_mode, hipStream_t st);
+
 hipError_t launch_add_emulated(const double* a, const double* b, double* out, int64_t n, hipStream_t st);
 hipError_t launch_fill_zero_f64(double* C, int64_t ldc, int64_t m, int64_t n, hipStream_t st);
 

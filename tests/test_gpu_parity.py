@@ -182,6 +182,37 @@ def test_dgemm_matches_oracle(fmt, m, n, k, k_block, s, phi, accum):
     ws.close()
 
 
+@pytest.mark.parametrize("accum", ["hw", "emu"])
+@pytest.mark.parametrize("fmt,m,n,k,k_block,s", [("fp8", 300, 270, 520, 0, 9), ("fp16", 130, 260, 700, 256, 5), ("fp6", 257, 64, 1000, 384, 8)])
+def test_scaled_dgemm_matches_oracle(fmt, m, n, k, k_block, s, accum):
+    """C = alpha (A B) + beta C: one rounded multiplication per term, one rounded addition, bit for bit."""
+    A, B = inputs.phi_pair(m, n, k, 1.0, seed=m + 3 * n + k)
+    rng = np.random.default_rng(m * n)
+    C0 = inputs.phi_matrix(m, n, 2.0, rng)
+    Ad, Bd = _upload(A, B)
+    ldc = m + 5
+    ws = device.Workspace.for_problem(m, n, k, FMT[fmt], s, k_block, scaled=True)
+    P = oz.ozaki_dgemm(A, B, fmt, s, k_block)
+    for alpha, beta in ((-2.5, 0.0), (1.0, 1.0), (0.3, -1.7), (0.0, 2.0), (1.0, 0.0)):
+        Cfull = np.full((n, ldc), np.nan)
+        if beta != 0.0:
+            Cfull[:, :m] = C0.T
+        Cd = torch.from_numpy(Cfull).cuda()
+        lib.ozaki_dgemm_scaled(m, n, k, alpha, Ad, m, Bd, k, beta, Cd, ldc, FMT[fmt], s, k_block, ACC[accum])
+        assert lib.ozaki_last_device_status() == 0
+        out = Cd.cpu().numpy()
+        assert np.all(np.isnan(out[:, m:]))
+        want = oz.ozaki_dgemm(A, B, fmt, s, k_block, alpha=alpha, beta=beta, C0=C0)
+        assert np.array_equal(out[:, :m].T.view(np.uint64), want.view(np.uint64)), (alpha, beta)
+        if (alpha, beta) == (1.0, 0.0):
+            assert np.array_equal(want.view(np.uint64), P.view(np.uint64))
+    # k = 0: the product is the zero matrix
+    Cd = torch.from_numpy(np.ascontiguousarray(C0.T)).cuda()
+    lib.ozaki_dgemm_scaled(m, n, 0, 3.0, Ad, m, Bd, 1, 0.5, Cd, m, FMT[fmt], s, k_block, ACC[accum])
+    assert np.array_equal(Cd.cpu().numpy().T.view(np.uint64), (3.0 * np.zeros((m, n)) + 0.5 * C0).view(np.uint64))
+    ws.close()
+
+
 @pytest.mark.parametrize("fmt,m,n,k,k_block,s,phi", [("fp8", 300, 270, 520, 0, 7, 1.0), ("fp16", 130, 260, 700, 256, 5, 2.0),
                                                      ("fp8", 64, 64, 4096, 0, 11, 0.5)])
 @pytest.mark.parametrize("accum", ["hw", "emu"])

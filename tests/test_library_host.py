@@ -88,6 +88,18 @@ def test_argument_errors_are_reported_before_anything_is_launched():
     assert f(0, 0, 5, None, 1, None, 1, None, 1, 0, 4, 0, 0) == 0        # empty product: nothing to do
     assert "workspace" in lib.status_string(lib.STATUS_WORKSPACE)
     assert "argument" in lib.status_string(-3)
+    # the scaled call counts positions in its own argument list (alpha is 4th, beta 9th)
+    g = lib.load().ozaki_dgemm_scaled
+    assert g(1, 1, -1, 2.0, None, 1, None, 1, 0.5, None, 1, 0, 4, 0, 0) == -3
+    assert g(1, 1, 1, float("inf"), None, 1, None, 1, 0.5, None, 1, 0, 4, 0, 0) == -4
+    assert g(1, 1, 1, 2.0, None, 1, None, 1, float("nan"), None, 1, 0, 4, 0, 0) == -9
+    assert g(1, 1, 1, 2.0, None, 1, None, 1, 5e-324, None, 1, 0, 4, 0, 0) == -9          # subnormal scalar
+    assert g(1, 1, 1, 2.0, None, 1, None, 1, 0.5, None, 1, 0, 4, 0, 0) == -10             # C missing
+    assert g(1, 1, 1, 2.0, None, 1, None, 1, 0.5, 1 << 20, 1, 0, 4, 0, 0) == -5           # A missing
+    assert g(1, 1, 1, 2.0, None, 1, None, 1, 0.5, None, 1, 9, 4, 0, 0) == -12             # bad format
+    assert g(1, 1, 1, 2.0, None, 1, None, 1, 0.5, None, 1, 0, 4, 0, 5) == -15             # bad accumulation mode
+    assert g(1, 1, 1, 2.0, 1 << 20, 1, 1 << 20, 1, 0.5, 1 << 20, 1, 0, 4, 0, 0) == lib.STATUS_WORKSPACE
+    assert lib.ozaki_workspace_bytes_scaled(1000, 500, 64, 0, 4, 0) - lib.ozaki_workspace_bytes(1000, 500, 64, 0, 4, 0) == 1000 * 500 * 8
 
 
 @pytest.fixture(scope="module")
@@ -122,6 +134,36 @@ def test_product_fp64_add_emulation_on_host_equals_fpu(host_emu):
     host_emu.host_fp64_add_emulated(a.ctypes.data_as(ctypes.c_void_p), b.ctypes.data_as(ctypes.c_void_p),
                                     out.ctypes.data_as(ctypes.c_void_p), ctypes.c_size_t(a.size))
     assert np.array_equal(out.view(np.uint64), (a + b).view(np.uint64))
+
+
+def test_product_fp64_mul_emulation_on_host_equals_fpu(host_emu):
+    rng = np.random.default_rng(9)
+    n = 1_000_000
+    a = _rnd(rng, 4 * n, -300, 300)
+    b = _rnd(rng, 4 * n, -300, 300)
+    # short significands: exact products and exact ties
+    a[n:2 * n] = np.ldexp(rng.integers(1, 1 << 27, n).astype(np.float64), rng.integers(-200, 200, n))
+    b[n:2 * n] = np.ldexp(rng.integers(1, 1 << 27, n).astype(np.float64), rng.integers(-200, 200, n))
+    # products next to a power of two
+    a[2 * n:3 * n] = np.nextafter(2.0, 0.0) * np.ldexp(1.0, rng.integers(-100, 100, n))
+    b[2 * n:3 * n] = (1.0 + np.ldexp(rng.integers(0, 8, n).astype(np.float64), -52)) * np.ldexp(1.0, rng.integers(-100, 100, n))
+    a[:4] = [0.0, -0.0, 3.0, -1.5]
+    b[:4] = [5.0, 2.0, 0.0, -0.0]
+    out = np.empty_like(a)
+    host_emu.host_fp64_mul_emulated(a.ctypes.data_as(ctypes.c_void_p), b.ctypes.data_as(ctypes.c_void_p),
+                                    out.ctypes.data_as(ctypes.c_void_p), ctypes.c_size_t(a.size))
+    assert np.array_equal(out.view(np.uint64), (a * b).view(np.uint64))
+    # the 128-bit product against Python integers (Section 4.2's four partial products)
+    x = rng.integers(0, 1 << 63, 20000, dtype=np.uint64) * np.uint64(2) + rng.integers(0, 2, 20000, dtype=np.uint64)
+    y = rng.integers(0, 1 << 63, 20000, dtype=np.uint64) * np.uint64(2) + rng.integers(0, 2, 20000, dtype=np.uint64)
+    x[:3] = [0, 2 ** 64 - 1, 2 ** 64 - 1]
+    y[:3] = [5, 2 ** 64 - 1, 1]
+    hi = np.empty_like(x)
+    lo = np.empty_like(x)
+    host_emu.host_mul_64x64_128(x.ctypes.data_as(ctypes.c_void_p), y.ctypes.data_as(ctypes.c_void_p),
+                                hi.ctypes.data_as(ctypes.c_void_p), lo.ctypes.data_as(ctypes.c_void_p), ctypes.c_size_t(x.size))
+    for xi, yi, h, l in zip(x.tolist(), y.tolist(), hi.tolist(), lo.tolist()):
+        assert (h << 64) | l == xi * yi
 
 
 def test_product_fp32_to_fp64_scaling_on_host(host_emu):

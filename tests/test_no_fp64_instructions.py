@@ -34,6 +34,11 @@ def test_emulated_accumulation_and_slicing_use_no_fp64(tmp_path):
     assert not re.search(r"\bv_\w*f64\w*", emu[0]), "FP64 instruction in the integer-emulated accumulation kernel"
     used = set(re.findall(r"\b(v_\w*f64\w*)", hw[0]))
     assert used and all(re.match(r"v_(add|ldexp|cvt)_", u) for u in used), used      # adds, exponent scaling, converts only
+    axpby_emu = [b for n, b in acc.items() if "axpby_kernelILb1" in n]
+    axpby_hw = [b for n, b in acc.items() if "axpby_kernelILb0" in n]
+    assert len(axpby_emu) == 1 and not re.search(r"\bv_\w*f64\w*", axpby_emu[0]), "FP64 instruction in the emulated scaling kernel"
+    used = set(re.findall(r"\b(v_\w*f64\w*)", axpby_hw[0]))
+    assert used and all(re.match(r"v_(add|mul)_f64", u) for u in used), used         # no fused multiply-add
     add_emu = [b for n, b in acc.items() if "add_emulated_kernel" in n]
     assert len(add_emu) == 1 and not re.search(r"\bv_\w*f64\w*", add_emu[0])
     split = _kernel_bodies("split.hip", tmp_path)
