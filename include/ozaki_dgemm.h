@@ -183,6 +183,19 @@ int ozaki_split(int is_B, int64_t rows, int64_t k, const double* X, int64_t ldx,
                 void* slices_out, int32_t* exps_out);
 
 /*
+ * ozaki_count_slices -- how many slices Eq. 4-8 extract from an operand "until x^(p) = 0" (Section 3, the
+ * paragraph before Eq. 4): the largest count over its vectors and k-blocks.  With that many slices (the larger
+ * of the two operands' counts) and OZAKI_PAIRS_ALL the sum of the pair products is the exact product, which is
+ * the error-free setting of the paper.
+ *   is_B, rows, k, X, ldx, slice_format, k_block   as for ozaki_split
+ *   count_out   HOST: the count; 0 for an all-zero operand; OZAKI_MAX_SLICES + 1 if OZAKI_MAX_SLICES slices do
+ *               not exhaust it (ozaki_dgemm cannot run the error-free setting on it then)
+ * Synchronises with the stream.  Workspace: 256 bytes, plus 8 * rows * k bytes (rounded up to 256) for A.
+ */
+int ozaki_count_slices(int is_B, int64_t rows, int64_t k, const double* X, int64_t ldx,
+                       int slice_format, int64_t k_block, int* count_out);
+
+/*
  * ozaki_pair_products -- the FP32 slice-pair products of Eq. 10-11, as the matrix unit produced them.
  *   P_out  DEVICE: float [T][pairs][n][m]: for block t and pair index z (pairs in accumulation order:
  *          anti-diagonals g = p+q from s+1 down to 2, p ascending within one), an m x n column-major

@@ -148,6 +148,20 @@ def slice_to_exhaustion(X: np.ndarray, rho: int, max_slices: int = 4096):
     return slices, cs
 
 
+def count_slices_to_exhaustion(X_rows: np.ndarray, fmt: str, k_block: int = 0) -> int:
+    """Largest number of slices any block of any row of X_rows yields before its remainder is zero."""
+    rows, k = X_rows.shape
+    if rows == 0 or k == 0:
+        return 0
+    plan = make_plan(k, fmt, k_block)
+    count = 0
+    for t in range(plan.num_blocks):
+        k0, k1 = t * plan.k_block, min(k, (t + 1) * plan.k_block)
+        sl, _ = slice_to_exhaustion(X_rows[:, k0:k1], plan.rho)
+        count = max(count, len(sl))
+    return count
+
+
 # --------------------------------------------------------------------------------------
 # Eq. 10-11: slice-pair products
 # --------------------------------------------------------------------------------------

@@ -35,6 +35,7 @@ SIGNATURES = {
     "ozaki_dgemm_scaled": (_int, [_i64, _i64, _i64, ctypes.c_double, _vp, _i64, _vp, _i64, ctypes.c_double, _vp, _i64, _int, _int,
                                   _i64, _int]),
     "ozaki_workspace_bytes_scaled": (_sz, [_i64, _i64, _i64, _int, _int, _i64]),
+    "ozaki_count_slices": (_int, [_int, _i64, _i64, _vp, _i64, _int, _i64, ctypes.POINTER(ctypes.c_int)]),
     "ozaki_set_stream": (_int, [_vp]),
     "ozaki_workspace_bytes": (_sz, [_i64, _i64, _i64, _int, _int, _i64]),
     "ozaki_workspace_min_bytes": (_sz, [_i64, _i64, _i64, _int, _int, _i64]),
@@ -148,6 +149,13 @@ def ozaki_dgemm_scaled(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, slice_forma
     st = load().ozaki_dgemm_scaled(m, n, k, float(alpha), _ptr(A), lda, _ptr(B), ldb, float(beta), _ptr(C), ldc, slice_format,
                                    num_slices, k_block, accum_mode)
     return _check(st, "ozaki_dgemm_scaled") if check else st
+
+
+def ozaki_count_slices(is_B, rows, k, X, ldx, slice_format, k_block) -> int:
+    """Slices until the remainder of every vector is zero (MAX_SLICES + 1: more than the library can use)."""
+    out = ctypes.c_int(0)
+    _check(load().ozaki_count_slices(is_B, rows, k, _ptr(X), ldx, slice_format, k_block, ctypes.byref(out)), "ozaki_count_slices")
+    return int(out.value)
 
 
 def ozaki_split(is_B, rows, k, X, ldx, slice_format, num_slices, k_block, slices_out, exps_out, check: bool = True) -> int:

@@ -399,6 +399,41 @@ int ozaki_split(int is_B, int64_t rows, int64_t k, const double* X, int64_t ldx,
     return 0;
 }
 
+int ozaki_count_slices(int is_B, int64_t rows, int64_t k, const double* X, int64_t ldx, int slice_format, int64_t k_block,
+                       int* count_out) {
+    if (is_B != 0 && is_B != 1) return -1;
+    if (rows < 0) return -2;
+    if (k < 0) return -3;
+    if (!count_out) return -8;
+    Plan pl;
+    const int st = make_plan(is_B ? 0 : rows, is_B ? rows : 0, k, slice_format, 1, k_block, false, pl);
+    if (st < 0) return st == -10 ? -6 : st == -12 ? -7 : st;
+    if (st != 0) return st;
+    *count_out = 0;
+    if (rows == 0 || k == 0) return 0;
+    if (!X) return -4;
+    if (ldx < (is_B ? (k > 1 ? k : 1) : (rows > 1 ? rows : 1))) return -5;
+    // needs the flag block and, for A, room for its transpose
+    const size_t need = FLAG_BYTES + (is_B ? 0 : align_up((size_t)rows * k * sizeof(double)));
+    if (!g.ws || g.ws_bytes < need) return OZAKI_STATUS_WORKSPACE;
+    int* flags = reinterpret_cast<int*>(g.ws);
+    HIP_TRY(hipMemsetAsync(flags + 1, 0, sizeof(int), g.stream));
+    const double* vecs = X;
+    int64_t ldv = ldx;
+    if (!is_B) {
+        double* At = reinterpret_cast<double*>(g.ws + FLAG_BYTES);
+        HIP_TRY(launch_transpose(X, ldx, rows, k, At, g.stream));
+        vecs = At;
+        ldv = k;
+    }
+    HIP_TRY(launch_count_slices(vecs, ldv, pl, rows, flags, g.stream));
+    int count = 0;
+    HIP_TRY(hipMemcpyAsync(&count, flags + 1, sizeof(int), hipMemcpyDeviceToHost, g.stream));
+    HIP_TRY(hipStreamSynchronize(g.stream));
+    *count_out = count;
+    return 0;
+}
+
 int ozaki_pair_products(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb,
                         int slice_format, int num_slices, int64_t k_block, float* P_out) {
     Plan pl;

@@ -141,6 +141,10 @@ hipError_t launch_transpose(const double* A, int64_t lda, int64_t m, int64_t k, 
 // Vectors are contiguous: vector r starts at X + r*ldv and has k entries.  Writes the internal layout.
 hipError_t launch_split(const double* X, int64_t ldv, const Plan& pl, const Operand& op, int* flags, hipStream_t st);
 
+// Slices until every remainder is zero (paragraph before Eq. 4): atomicMax of the per-vector count into flags[1]
+// (which the caller has cleared); MAX_SLICES + 1 means that MAX_SLICES slices do not exhaust some vector.
+hipError_t launch_count_slices(const double* X, int64_t ldv, const Plan& pl, int64_t rows, int* flags, hipStream_t st);
+
 // Internal layout -> plain vector-major codes (verification export).
 hipError_t launch_export_slices(const Plan& pl, const Operand& op, void* out, hipStream_t st);
 

@@ -48,9 +48,9 @@ struct SplitArgs {
     int64_t chunks;        // chunks per block
     int s, b;
     int vec_ok;            // 16-byte aligned loads allowed
-    uint8_t* slices;
+    uint8_t* slices;       // null: count only, nothing is stored
     int32_t* exps;
-    int* flags;
+    int* flags;            // [0]: non-finite input seen; [1]: slice count (count-only mode)
 };
 
 constexpr int NO_ELEM = -(1 << 30);
@@ -170,6 +170,11 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
                 cmax = o > cmax ? o : cmax;
             }
         }
+        if (a.slices == nullptr) {
+            // count-only mode ("until x^(p) = 0", paragraph before Eq. 4): something is left before the (p+1)-th
+            // slice, so this vector needs at least p + 1 of them
+            if (cmax != NO_ELEM && tr == 0) atomicMax(a.flags + 1, p + 1);
+        }
         const int c = (cmax == NO_ELEM) ? 0 : cmax;
         const int unit = c - a.b;                                      // the slice's unit is 2^(c-b)
         // remainders of active elements were left in units of the previous slice: rescale them to this one (a
@@ -243,7 +248,7 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
                 uint64_t w48 = 0;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) w48 |= (uint64_t)encode_e2m3(qs[e], a.b) << (6 * e);
-                if (ke < padded) {
+                if (ke < padded && a.slices != nullptr) {
                     const int64_t kc = ke / EPC;
                     const int o = (int)((ke % EPC) / 8), g = o >> 2, j = o & 3;
                     uint8_t* const chunk = dst_slice + (size_t)kc * a.rows_pad * ROWB;
@@ -259,7 +264,7 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
                 uint32_t c2[4];                                            // two codes each
 #pragma unroll
                 for (int e = 0; e < 4; ++e) c2[e] = encode_type2_pair<FP16>(qs[2 * e], qs[2 * e + 1], a.b);
-                if (ke < padded) {
+                if (ke < padded && a.slices != nullptr) {
                     const int64_t kc = ke / EPC;
                     uint8_t* dst = dst_slice + ((size_t)kc * a.rows_pad + row) * CHUNK_BYTES + (ke % EPC) * (FP16 ? 2 : 1);
                     if (FP16) {
@@ -278,7 +283,7 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
                 }
             }
         }
-        if (tr == 0) a.exps[(t * a.s + p) * a.rows_pad + row] = c;
+        if (tr == 0 && a.slices != nullptr) a.exps[(t * a.s + p) * a.rows_pad + row] = c;
         // this thread's candidate for the next exponent: remainders are rmax * 2^(unit - F)
         cmax = cdorm;
         if (rmax != 0) {
@@ -378,6 +383,16 @@ hipError_t launch_split(const double* X, int64_t ldv, const Plan& pl, const Oper
     if (octets <= 2048) return launch_split_cfg<2, 1024>(a, fmt, pl.T, st);
     if (octets <= 4096) return launch_split_cfg<4, 1024>(a, fmt, pl.T, st);
     return hipErrorInvalidValue;                                                // the planner rejects longer blocks
+}
+
+hipError_t launch_count_slices(const double* X, int64_t ldv, const Plan& pl, int64_t rows, int* flags, hipStream_t st) {
+    Plan cp = pl;
+    cp.s = MAX_SLICES + 1;                       // one more than the library can use: "not exhausted" is reported as 33
+    Operand op;
+    op.rows = rows;
+    op.rows_pad = (rows + TILE - 1) / TILE * TILE;
+    op.slices = nullptr; op.exps = nullptr; op.deltas = nullptr;
+    return launch_split(X, ldv, cp, op, flags, st);
 }
 
 hipError_t launch_deltas(const Plan& pl, const Operand& op, hipStream_t st) {

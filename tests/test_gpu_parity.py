@@ -6,6 +6,8 @@ which is checked too, against the exact big-integer product).
 """
 import math
 
+from fractions import Fraction
+
 import numpy as np
 import pytest
 
@@ -180,6 +182,49 @@ def test_dgemm_matches_oracle(fmt, m, n, k, k_block, s, phi, accum):
     if s >= 7:
         assert e_ab <= 4 * k * 2.0 ** -53
     ws.close()
+
+
+def test_slice_count_until_exhaustion_and_error_free_product():
+    """The paper's own stopping rule (slice until the remainder is zero) and its consequence: with that many
+    slices and all pairs, the pair products sum to the exact product (Eq. 9-10)."""
+    rng = np.random.default_rng(77)
+    cases = [
+        ("fp8", inputs.uniform_1_10(70, 300, rng), 0),
+        ("fp8", inputs.phi_matrix(33, 1000, 1.0, rng), 384),
+        ("fp16", inputs.uniform_1_10(40, 2100, rng), 1024),
+        ("fp6", inputs.full_mantissa_one_binade(20, 512, rng), 0),
+        ("fp8", np.round(rng.uniform(-16, 16, (10, 64))) * 2.0 ** 7, 0),       # integers: one slice
+        ("fp8", np.zeros((5, 40)), 0),
+        ("fp16", inputs.phi_matrix(9, 64, 6.0, rng), 0),
+        ("fp8", inputs.phi_matrix(9, 64, 30.0, np.random.default_rng(5)), 0),   # exponent range too wide for 32 slices
+    ]
+    for fmt, X, kb in cases:
+        rows, k = X.shape
+        want = oz.count_slices_to_exhaustion(X, fmt, kb)
+        for is_B in (0, 1):
+            Xd = torch.from_numpy(np.ascontiguousarray(X if is_B else X.T)).cuda()      # column-major k x rows / rows x k
+            ws = device.Workspace(256 + 8 * rows * k + 256)
+            got = lib.ozaki_count_slices(is_B, rows, k, Xd, k if is_B else rows, FMT[fmt], kb)
+            ws.close()
+            assert got == min(want, lib.MAX_SLICES + 1), (fmt, rows, k, kb, is_B, got, want)
+    # error-free product on a small case: every entry of C is the correctly rounded exact value
+    A = inputs.uniform_1_10(40, 96, rng)
+    B = inputs.uniform_1_10(96, 24, rng)
+    Ad, Bd = _upload(A, B)
+    ws = device.Workspace(1 << 20)
+    s = max(lib.ozaki_count_slices(0, 40, 96, Ad, 40, FMT["fp8"], 0), lib.ozaki_count_slices(1, 24, 96, Bd, 96, FMT["fp8"], 0))
+    ws.close()
+    assert s == max(oz.count_slices_to_exhaustion(A, "fp8"), oz.count_slices_to_exhaustion(B.T.copy(), "fp8")) <= lib.MAX_SLICES
+    ws = device.Workspace.for_problem(40, 24, 96, FMT["fp8"], s | lib.PAIRS_ALL, 0)
+    Cd = torch.empty((24, 40), dtype=torch.float64, device="cuda")
+    lib.ozaki_dgemm(40, 24, 96, Ad, 40, Bd, 96, Cd, 40, FMT["fp8"], s | lib.PAIRS_ALL, 0, ACC["emu"])
+    C = Cd.cpu().numpy().T
+    ws.close()
+    assert np.array_equal(C.view(np.uint64), oz.ozaki_dgemm(A, B, "fp8", s, 0, mode="full").view(np.uint64))
+    for i in range(0, 40, 7):
+        for j in range(0, 24, 5):
+            ex = exact.exact_dot(A[i, :], B[:, j])
+            assert abs(Fraction(float(C[i, j])) - ex) <= Fraction(float(np.spacing(abs(C[i, j])))) , (i, j)
 
 
 @pytest.mark.parametrize("accum", ["hw", "emu"])
