@@ -468,3 +468,38 @@ def test_full_size_configs_on_sampled_rows_and_columns(name):
     ws.close()
     del Cd, ws
     torch.cuda.empty_cache()
+
+
+def test_dgemm_can_be_captured_in_a_hip_graph_and_replayed():
+    """ozaki_dgemm only enqueues kernels on the library stream (no allocation, no synchronisation, no memset), so a
+    caller can capture it; every replay must give the eager result, also with other work between the replays."""
+    m, n, k, s = 300, 270, 520, 9
+    A, B = inputs.phi_pair(m, n, k, 1.0, seed=11)
+    A2, B2 = inputs.phi_pair(m, n, k, 2.0, seed=12)
+    Ad, Bd = _upload(A, B)
+    Cd = torch.zeros((n, m), dtype=torch.float64, device="cuda")
+    ws = device.Workspace.for_problem(m, n, k, FMT["fp8"], s, 0)
+    want = [oz.ozaki_dgemm(A, B, "fp8", s, 0), oz.ozaki_dgemm(A2, B2, "fp8", s, 0)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        lib.ozaki_set_stream(side.cuda_stream)
+        lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, FMT["fp8"], s, 0, ACC["emu"])      # warm-up outside the capture
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, FMT["fp8"], s, 0, ACC["emu"])
+    torch.cuda.synchronize()
+    for rep in range(4):
+        src = (A, B) if rep % 2 == 0 else (A2, B2)
+        Ad.copy_(torch.from_numpy(np.ascontiguousarray(src[0].T)).cuda())                 # eager work between the replays
+        Bd.copy_(torch.from_numpy(np.ascontiguousarray(src[1].T)).cuda())
+        Cd.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = Cd.cpu().numpy().T
+        assert np.array_equal(got.view(np.uint64), want[rep % 2].view(np.uint64)), rep
+    lib.ozaki_set_stream(torch.cuda.current_stream().cuda_stream)
+    assert lib.ozaki_last_device_status() == 0
+    ws.close()
