@@ -105,7 +105,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); "
-              "multi-GPU sharding is described in DESIGN.md but not implemented", file=sys.stderr)
+              "sharding over several GPUs is not implemented", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch

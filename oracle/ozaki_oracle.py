@@ -8,7 +8,7 @@ Follows the paper's Section 3 in its order and notation:
   accumulate  sum of 2^(c_x+c_y) * product        Eq. 10, in Type1 = FP64 arithmetic (Section 3, last paragraphs)
   blocking    the above per block of the inner dimension, block results summed in FP64   Section 4.3
 
-Conventions (this build's readings of points the paper leaves open are listed in the design notes):
+Conventions (where the paper leaves a point open, the reading taken is stated here):
   * A is m x k, B is k x n, both given as ordinary numpy arrays (logical indexing A[i, kk], B[kk, j]).
   * Slices of A are taken per row of A, slices of B per column of B, over one k-block at a time.
   * b = 53 - rho is the number of magnitude bits of a slice entry: entry = q * 2^-b, q integer, |q| <= 2^b.
