@@ -259,7 +259,9 @@ def test_scaled_dgemm_matches_oracle(fmt, m, n, k, k_block, s, accum):
 
 
 @pytest.mark.parametrize("fmt,m,n,k,k_block,s,phi", [("fp8", 300, 270, 520, 0, 7, 1.0), ("fp16", 130, 260, 700, 256, 5, 2.0),
-                                                     ("fp8", 64, 64, 4096, 0, 11, 0.5)])
+                                                     ("fp8", 64, 64, 4096, 0, 11, 0.5),
+                                                     ("fp8", 70, 50, 200, 0, 32, 6.0),        # the largest slice count
+                                                     ("fp6", 70, 50, 200, 64, 32, 6.0)])
 @pytest.mark.parametrize("accum", ["hw", "emu"])
 def test_all_pairs_mode_matches_oracle(fmt, m, n, k, k_block, s, phi, accum):
     """num_slices | PAIRS_ALL: all s*s slice pairs (the paper's setting), anti-diagonals 2s ... 2."""
