@@ -226,10 +226,11 @@ def block_result(Ab: np.ndarray, Bb: np.ndarray, plan: Plan, num_slices: int, mo
                  add: Callable = hw_add, keep: bool = True, group: bool = True) -> BlockResult:
     """One k-block: slice rows of Ab (m x kb) and columns of Bb (kb x n), form the pair products, accumulate.
 
-    Accumulation (element by element): the pairs are visited in `pair_order`.  With `group` set, every
-    anti-diagonal is cut into consecutive chunks of `run_limit` pairs; inside a chunk, consecutive pairs
-    whose scale factor 2^(c_x+c_y) is the same for that element are first summed exactly (an integer sum
-    that would also be exact in FP32, Eq. 11) and each such run is then added with one FP64 addition.
+    Accumulation (element by element): the pairs are visited in `pair_order`.  With `group` set, consecutive
+    pairs of one anti-diagonal whose scale factor 2^(c_x+c_y) is the same for that element are first summed
+    exactly (integers in units of 2^-2b; a device may form such sums in the matrix unit as far as the FP32
+    window of Eq. 11 allows, see `run_limit`, and in integer registers beyond it -- exact sums do not depend
+    on how they are formed) and each such run is then added with one rounded FP64 addition.
     Without `group` every product is added on its own.
     """
     sa, ca, _ = slice_rows(Ab, plan.rho, num_slices)
@@ -241,15 +242,14 @@ def block_result(Ab: np.ndarray, Bb: np.ndarray, plan: Plan, num_slices: int, mo
     S = np.zeros(shape, dtype=np.float64)
     pairs = pair_order(num_slices, mode)
     products = []
-    gmax = run_limit(plan) if group else 1
     run_sum = np.zeros(shape, dtype=np.int64)          # exact sum of the current run, in units of 2^(run_e)
     run_e = np.zeros(shape, dtype=np.int64)
     open_run = np.zeros(shape, dtype=bool)
-    run_diag, pos = None, 0                            # anti-diagonal of the previous pair, position inside it
+    run_diag = None                                    # anti-diagonal of the previous pair
 
     def flush(mask):
         nonlocal S
-        term = np.where(mask, np.ldexp(run_sum.astype(np.float64), run_e), 0.0)   # exact: |run_sum| <= 2^24
+        term = np.where(mask, np.ldexp(run_sum.astype(np.float64), run_e), 0.0)   # exact: |run_sum| < 2^53
         S = add(S, term)                                                           # adding +0.0 changes nothing
 
     for (p, q) in pairs:
@@ -257,16 +257,13 @@ def block_result(Ab: np.ndarray, Bb: np.ndarray, plan: Plan, num_slices: int, mo
         if P.size and np.max(np.abs(P)) > limit:
             raise AssertionError("pair product exceeds the exact FP32 range (Eq. 11 violated)")
         e = (ca[p - 1][:, None] + cb[q - 1][None, :] - 2 * plan.b).astype(np.int64)   # 2^(c_x+c_y) * 2^-2b
-        pos = pos + 1 if run_diag == p + q else 0
+        same_diag = group and run_diag == p + q        # a new anti-diagonal ends every run
         run_diag = p + q
-        inside_chunk = pos % gmax != 0                 # a chunk boundary (or a new anti-diagonal) ends every run
-        cont = open_run & inside_chunk & (e == run_e)
+        cont = open_run & same_diag & (e == run_e)
         flush(open_run & ~cont)
         run_sum = np.where(cont, run_sum + P, P)
         run_e = e
         open_run = np.ones(shape, dtype=bool)
-        if run_sum.size and np.max(np.abs(run_sum)) > limit:
-            raise AssertionError("a run of pair products exceeds the exact FP32 range")
         if keep:
             products.append(P)
     flush(open_run)

@@ -3,11 +3,11 @@
 //
 // For one k-block, element (i, j), the pairs (p, q) are visited least significant anti-diagonal first, p
 // ascending inside one.  The term of a pair is P_pq(i,j) * 2^e with e = (cA_p(i) - cA_1(i)) + (cB_q(j) - cB_1(j)).
-// Every anti-diagonal is cut into groups of at most run_limit consecutive pairs; inside a group, consecutive
-// pairs with the same e form a run, whose sum stays inside the exact FP32 window of Eq. 11.  A run is summed
-// exactly (a 32-bit integer in units of 2^-2b) and added to the block sum S with ONE rounded FP64 addition.
-// Where a whole group has one scale for every element of a tile, the GEMM kernel has already formed the run's
-// sum in the matrix unit's accumulators and stored it once.  Then
+// Inside an anti-diagonal, consecutive pairs with the same e form a run.  A run is summed exactly (a 32-bit
+// integer in units of 2^-2b: at most 32 products of at most 2^24 units each) and added to the block sum S with
+// ONE rounded FP64 addition.  The GEMM kernel has already formed part of these sums in the matrix unit's
+// accumulators, as far as the exact FP32 window of Eq. 11 reaches (groups of at most run_limit pairs) and where a
+// whole tile shares the scale; the rest is merged here, element by element.  Then
 //     C   = S * 2^(cA_1(i) + cB_1(j))            first block
 //     C  += S * 2^(cA_1(i) + cB_1(j))            later blocks (one more FP64 addition)
 // Scaling by a power of two commutes with rounding (inside the normal range), so summing with exponents
@@ -57,7 +57,7 @@ template <bool EMU>
 __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
     __shared__ int relA[MAX_SLICES][32];
     __shared__ int relB[MAX_SLICES][32];
-    __shared__ uint32_t entries[MAX_PAIRS];           // stored runs of this tile: slot | p << 12 | q << 18 | first-of-group << 24
+    __shared__ uint32_t entries[MAX_PAIRS];           // stored runs of this tile: slot | p << 12 | q << 18 | first-of-diagonal << 24
     __shared__ int n_entries;
 
     const int tid = threadIdx.x;
@@ -108,8 +108,8 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
             uint32_t entry = 0;
             if (tid < len) {
                 const int p = diag_first_p(a.order, g) + tid - 1, q = g - p - 2;     // 0-based slice indices
-                const bool first = tid % a.order.run_limit == 0;
-                start = first || !(a.allow_chain && pair_linked(dA, dB, p - 1, q + 1));
+                const bool first = tid == 0;                                        // first pair of the anti-diagonal: ends every run
+                start = tid % a.order.run_limit == 0 || !(a.allow_chain && pair_linked(dA, dB, p - 1, q + 1));   // stored on its own
                 entry = (uint32_t)(slot0 + tid) | ((uint32_t)p << 12) | ((uint32_t)q << 18) | ((uint32_t)first << 24);
             }
             const unsigned long long mask = __ballot(start);
@@ -130,9 +130,9 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
             S[r] = (acc_t)((double)S[r] + ldexp((double)run_sum, run_e - a.two_b));
         }
     };
-    // Per element, consecutive stored runs of one group with the same scale are merged further (32-bit integer,
-    // units of 2^-p_frac) before the FP64 addition: together with the tile-wide runs formed by the GEMM kernel this
-    // is the element-wise rule "consecutive pairs of a group with equal scale are summed exactly".
+    // Per element, consecutive stored runs of one anti-diagonal with the same scale are merged further (32-bit
+    // integer, units of 2^-p_frac) before the FP64 addition: together with the tile-wide runs formed by the GEMM
+    // kernel this is the element-wise rule "consecutive pairs of an anti-diagonal with equal scale are summed exactly".
     int run_sum[4] = {0, 0, 0, 0}, run_e[4] = {0, 0, 0, 0};
     auto process = [&](uint32_t entry, const uint4& v) {
         const int p = (entry >> 12) & 63, q = (entry >> 18) & 63;

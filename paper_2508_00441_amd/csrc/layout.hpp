@@ -64,9 +64,11 @@ struct Plan {
 
 // The slice pairs (p, q), 1-based, and their accumulation order: anti-diagonals g = p + q from the least
 // significant (largest g) down to g = 2, p ascending inside one.  Triangle mode uses the pairs with p + q <= s + 1,
-// full mode all s * s.  Every anti-diagonal is cut into groups of at most run_limit consecutive pairs (the unit
-// whose equal-scale products are summed exactly before the FP64 addition); pairs are numbered z = 0, 1, ... in this
-// order.  Everything below is a closed form of (s, full, run_limit), evaluated on the host and in the kernels.
+// full mode all s * s.  Consecutive pairs of an anti-diagonal with equal scale are summed exactly before the FP64
+// addition; the matrix unit can do that for at most run_limit pairs (the exact FP32 window), so every anti-diagonal is
+// cut into groups of at most run_limit consecutive pairs, the unit of work of the GEMM kernel; pairs are numbered
+// z = 0, 1, ... in this order.  Everything below is a closed form of (s, full, run_limit), evaluated on the host and
+// in the kernels.
 struct PairOrder {
     int s;
     int full;

@@ -334,8 +334,8 @@ def test_scaling_and_permutation_invariants():
 
 def test_equal_scale_runs_are_summed_exactly_before_the_fp64_addition():
     """Rows/columns inside one binade follow a regular exponent ladder, so every anti-diagonal carries one
-    scale factor; the grouped accumulation must then equal: exact sum of each run of at most run_limit
-    products inside a chunk of run_limit pairs (rational arithmetic here), one FP64 addition per run."""
+    scale factor; the grouped accumulation must then equal: exact sum of each run of equal-scale products
+    inside an anti-diagonal (rational arithmetic here), one FP64 addition per run."""
     rng = np.random.default_rng(31)
     m, n, k = 4, 3, 64
     A = inputs.full_mantissa_one_binade(m, k, rng) * np.where(rng.random((m, k)) < 0.5, -1.0, 1.0)
@@ -350,16 +350,17 @@ def test_equal_scale_runs_are_summed_exactly_before_the_fp64_addition():
             S = np.zeros((m, n))
             for i in range(m):
                 for j in range(n):
-                    run, run_scale, run_open, run_diag, pos, acc = Fraction(0), None, False, None, 0, 0.0
+                    run, run_scale, run_open, run_diag, acc, n_adds = Fraction(0), None, False, None, 0.0, 0
                     for (p, q), P in zip(br.pairs, br.products):
                         scale = int(br.c_a[p - 1][i] + br.c_b[q - 1][j])
-                        pos = pos + 1 if p + q == run_diag else 0
-                        if run_open and (scale != run_scale or pos % gmax == 0):
-                            acc = acc + float(run)          # float(Fraction) is exact here: a 25-bit integer times 2^e
+                        if run_open and (scale != run_scale or p + q != run_diag):
+                            acc = acc + float(run)          # float(Fraction) is exact here: a short integer times 2^e
+                            n_adds += 1
                             run = Fraction(0)
                         run += Fraction(int(P[i, j])) * Fraction(2) ** (scale - 2 * plan.b)
                         run_scale, run_diag, run_open = scale, p + q, True
                     S[i, j] = acc + float(run)
+                    assert n_adds + 1 == len({p + q for p, q in br.pairs})      # regular ladder: one addition per anti-diagonal
             want = want + S
         assert np.array_equal(C.view(np.uint64), want.view(np.uint64)), fmt
         # the ladder is regular here: fewer FP64 additions than pairs, and never a worse result than pair-by-pair
