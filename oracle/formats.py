@@ -24,7 +24,7 @@ import numpy as np
 SIGNIFICAND_BITS = {"fp8": 4, "fp16": 11, "fp6": 4, "fp6_e3m2": 3}
 
 #: the stored code holds slice * 2^CODE_SHIFT (nonzero only for FP6 E2M3, see above)
-CODE_SHIFT = {"fp8": 0, "fp16": 0, "fp6": 1}
+CODE_SHIFT = {"fp8": 0, "fp16": 0, "fp6": 1, "fp6_e3m2": 0}
 
 
 def e4m3_decode_table() -> np.ndarray:
@@ -118,10 +118,49 @@ def e2m3_encode_exact(values: np.ndarray) -> np.ndarray:
     return out
 
 
+def e3m2_decode_table() -> np.ndarray:
+    """Value of each of the 64 OCP E3M2 codes (1 sign, 3 exponent bits with bias 3, 2 fraction bits, no Inf/NaN):
+    the FP6 flavour of the paper's Table 2."""
+    vals = np.empty(64, dtype=np.float64)
+    for code in range(64):
+        sign = -1.0 if code & 0x20 else 1.0
+        e = (code >> 2) & 0x7
+        f = code & 0x3
+        if e == 0:
+            vals[code] = sign * (f / 4.0) * 2.0 ** (1 - 3)          # subnormal
+        else:
+            vals[code] = sign * (1.0 + f / 4.0) * 2.0 ** (e - 3)    # normal
+    return vals
+
+
+_E3M2_VALUES = e3m2_decode_table()
+
+
+def e3m2_decode(codes: np.ndarray) -> np.ndarray:
+    return _E3M2_VALUES[np.asarray(codes, dtype=np.uint8)]
+
+
+def e3m2_encode_exact(values: np.ndarray) -> np.ndarray:
+    values = np.asarray(values, dtype=np.float64)
+    out = np.zeros(values.shape, dtype=np.uint8)
+    found = values == 0
+    for code in range(64):
+        if code in (0x00, 0x20):
+            continue
+        hit = values == _E3M2_VALUES[code]
+        out[hit] = code
+        found |= hit
+    if not found.all():
+        raise ValueError(f"value not representable in FP6 E3M2: {values[~found].ravel()[:4]}")
+    return out
+
+
 def encode_exact(fmt: str, values: np.ndarray) -> np.ndarray:
     """Codes of the slice values `values` (= q * 2^-b, Eq. 8) in format `fmt`."""
     if fmt == "fp6":
         return e2m3_encode_exact(np.asarray(values, dtype=np.float64) * 2.0 ** CODE_SHIFT["fp6"])
+    if fmt == "fp6_e3m2":
+        return e3m2_encode_exact(values)
     if fmt == "fp8":
         return e4m3_encode_exact(values)
     if fmt == "fp16":
@@ -133,6 +172,8 @@ def decode(fmt: str, codes: np.ndarray) -> np.ndarray:
     """Slice values (= q * 2^-b) of the codes."""
     if fmt == "fp6":
         return e2m3_decode(codes) * 2.0 ** -CODE_SHIFT["fp6"]
+    if fmt == "fp6_e3m2":
+        return e3m2_decode(codes)
     if fmt == "fp8":
         return e4m3_decode(codes)
     if fmt == "fp16":

@@ -111,7 +111,8 @@ def _nasty_rows(rng, rows, k):
     return X
 
 
-@pytest.mark.parametrize("fmt,k", [("fp8", 64), ("fp16", 64), ("fp16", 1024), ("fp8", 4096), ("fp6", 64), ("fp6", 4096)])
+@pytest.mark.parametrize("fmt,k", [("fp8", 64), ("fp16", 64), ("fp16", 1024), ("fp8", 4096), ("fp6", 64), ("fp6", 4096),
+                                   ("fp6_e3m2", 64), ("fp6_e3m2", 4096)])
 def test_slices_sum_back_exactly_and_fit_their_format(fmt, k):
     rng = np.random.default_rng(11)
     X = _nasty_rows(rng, 12, k)
@@ -205,6 +206,22 @@ def test_e2m3_table_has_the_published_format_constants():
         formats.encode_exact("fp6", np.array([17 / 16.0]))
 
 
+def test_e3m2_table_has_the_published_format_constants():
+    """OCP microscaling FP6 E3M2 (Table 2's FP6 column): bias 3, no infinities/NaNs, subnormals 1/16 .. 3/16,
+    normals 0.25 .. 28; three significand bits, so b = 3 and the slice values q/8 (|q| <= 8) are all codes."""
+    vals = formats.e3m2_decode(np.arange(64, dtype=np.uint8))
+    assert np.all(np.isfinite(vals))
+    pos = vals[:32]
+    assert np.array_equal(vals[32:], -pos) and np.all(np.diff(pos) > 0)
+    assert pos[0] == 0.0 and pos[1] == 0.0625 and pos[3] == 0.1875 and pos[4] == 0.25 and pos[31] == 28.0
+    assert oz.make_plan(4096, "fp6_e3m2").b == 3 and oz.make_plan(1 << 18, "fp6_e3m2").b == 3 and oz.make_plan(1 << 19, "fp6_e3m2").b == 2
+    sl = np.arange(-8, 9) / 8.0
+    codes = formats.encode_exact("fp6_e3m2", sl)
+    assert codes.max() < 64 and np.array_equal(formats.decode("fp6_e3m2", codes), sl)
+    with pytest.raises(ValueError):
+        formats.encode_exact("fp6_e3m2", np.array([9 / 16.0]))          # needs four significand bits
+
+
 def test_fp6_e2m3_has_the_slice_width_of_e4m3_and_gives_the_same_bits():
     """Four significand bits either way (Eq. 2), so plan, slices, exponents, products and C coincide."""
     for k, kb in ((8, 0), (4096, 0), (65536, 0), (262144, 0), (1000, 384)):
@@ -241,7 +258,7 @@ def _exact_sum_of_terms(blocks, b):
     return tot
 
 
-@pytest.mark.parametrize("fmt,kblock", [("fp8", 0), ("fp16", 0), ("fp8", 16), ("fp16", 10), ("fp6", 0), ("fp6", 16)])
+@pytest.mark.parametrize("fmt,kblock", [("fp8", 0), ("fp16", 0), ("fp8", 16), ("fp16", 10), ("fp6", 0), ("fp6", 16), ("fp6_e3m2", 0)])
 def test_all_slices_all_pairs_equal_the_exact_product(fmt, kblock):
     """Eq. 10 with every slice and every pair is an identity: brute force on tiny, non-square inputs."""
     rng = np.random.default_rng(21)
