@@ -34,11 +34,13 @@ extern "C" {
 enum {
     OZAKI_SLICE_FP8_E4M3 = 0, /* OCP E4M3, 4 significand bits, FP32 accumulation (Section 4.1)        */
     OZAKI_SLICE_FP16 = 1,     /* IEEE binary16, 11 significand bits, FP32 accumulation (Section 4.1)  */
-    OZAKI_SLICE_FP6_E2M3 = 2  /* OCP microscaling FP6 E2M3 (bias 1, no Inf/NaN): the 4 significand bits */
+    OZAKI_SLICE_FP6_E2M3 = 2, /* OCP microscaling FP6 E2M3 (bias 1, no Inf/NaN): the 4 significand bits */
                               /* of E4M3, so the same slices and the same C as OZAKI_SLICE_FP8_E4M3,    */
                               /* on the twice as fast FP6 path of the matrix unit that Section 4.1      */
                               /* points to.  E2M3's smallest step is 1/8: a code holds twice the value  */
                               /* of Eq. 8, and the factor 1/4 per product is applied with the exponents */
+    OZAKI_SLICE_FP6_E3M2 = 3  /* OCP microscaling FP6 E3M2 (bias 3), 3 significand bits: the FP6 column of    */
+                              /* Table 2 (14 slices for a full FP64 significand); same FP6 matrix path        */
 };
 
 /* How the slice-pair products are summed into FP64 (Section 3 after Eq. 11; Section 4.2). */

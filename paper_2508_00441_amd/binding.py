@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libozaki.so")
 SLICE_FP8_E4M3 = 0
 SLICE_FP16 = 1
 SLICE_FP6_E2M3 = 2
+SLICE_FP6_E3M2 = 3
 ACCUM_FP64_HW = 0
 ACCUM_FP64_INT_EMU = 1
 STATUS_OK, STATUS_INFEASIBLE, STATUS_WORKSPACE, STATUS_HIP_ERROR, STATUS_NONFINITE = 0, 1, 3, 4, 5
@@ -24,7 +25,7 @@ PAIRS_ALL = 0x100
 MAX_SLICES = 32
 MAX_K_BLOCK = 32768
 
-SLICE_FORMATS = {"fp8": SLICE_FP8_E4M3, "fp16": SLICE_FP16, "fp6": SLICE_FP6_E2M3}
+SLICE_FORMATS = {"fp8": SLICE_FP8_E4M3, "fp16": SLICE_FP16, "fp6": SLICE_FP6_E2M3, "fp6_e3m2": SLICE_FP6_E3M2}
 ACCUM_MODES = {"hw": ACCUM_FP64_HW, "emu": ACCUM_FP64_INT_EMU}
 
 #: every symbol include/ozaki_dgemm.h declares: name -> (restype, argtypes)

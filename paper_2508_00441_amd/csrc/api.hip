@@ -39,7 +39,8 @@ int fail_hip(hipError_t e) {
 
 // Largest b <= m2 with kb * 4^b <= 2^24 (Eq. 1-3 with Type1 = FP64, Type3 = FP32); -1 if none.
 int slice_bits(int64_t kb, int fmt) {
-    const int m2 = fmt == OZAKI_SLICE_FP16 ? 11 : 4;          // E4M3 and E2M3: three fraction bits and the hidden one
+    // significand bits with the hidden one: E4M3 and E2M3 have three fraction bits, E3M2 two
+    const int m2 = fmt == OZAKI_SLICE_FP16 ? 11 : fmt == OZAKI_SLICE_FP6_E3M2 ? 3 : 4;
     for (int b = m2; b >= 0; --b)
         if (kb <= ((int64_t)1 << (24 - 2 * b))) return b;
     return -1;
@@ -50,13 +51,13 @@ int make_plan(int64_t m, int64_t n, int64_t k, int fmt, int s, int64_t k_block, 
     if (m < 0) return -1;
     if (n < 0) return -2;
     if (k < 0) return -3;
-    if (fmt != OZAKI_SLICE_FP8_E4M3 && fmt != OZAKI_SLICE_FP16 && fmt != OZAKI_SLICE_FP6_E2M3) return -10;
+    if (fmt < OZAKI_SLICE_FP8_E4M3 || fmt > OZAKI_SLICE_FP6_E3M2) return -10;
     if (s < 0 || s > 0xFF) return -11;
     if (k_block < 0) return -12;
     memset(&pl, 0, sizeof(pl));
     pl.m = m; pl.n = n; pl.k = k; pl.fmt = fmt;
     pl.epc = fmt == OZAKI_SLICE_FP16 ? CHUNK_BYTES / 2 : CHUNK_BYTES;
-    pl.row_bytes = fmt == OZAKI_SLICE_FP6_E2M3 ? CHUNK_BYTES_FP6 : CHUNK_BYTES;
+    pl.row_bytes = fmt_is_fp6(fmt) ? CHUNK_BYTES_FP6 : CHUNK_BYTES;
     pl.kb = (k_block == 0 || k_block > k) ? k : k_block;
     if (pl.kb < 1) pl.kb = 1;
     if (pl.kb > MAX_K_BLOCK) return OZAKI_STATUS_INFEASIBLE;
@@ -269,7 +270,7 @@ extern "C" {
 
 int ozaki_plan(int64_t k_block, int slice_format, int* rho_out, int* bits_out) {
     if (k_block < 1) return -1;
-    if (slice_format != OZAKI_SLICE_FP8_E4M3 && slice_format != OZAKI_SLICE_FP16 && slice_format != OZAKI_SLICE_FP6_E2M3) return -2;
+    if (slice_format < OZAKI_SLICE_FP8_E4M3 || slice_format > OZAKI_SLICE_FP6_E3M2) return -2;
     const int b = slice_bits(k_block, slice_format);
     if (b < 0) return OZAKI_STATUS_INFEASIBLE;
     if (rho_out) *rho_out = 53 - b;

@@ -17,7 +17,8 @@ constexpr int CHUNK_BYTES_FP6 = 48;       // the same 64 inner indices as 6-bit 
 constexpr int TILE_ELEMS = TILE * TILE;
 
 // slice formats (values of ozaki_slice_format)
-constexpr int FMT_FP8 = 0, FMT_FP16 = 1, FMT_FP6 = 2;
+constexpr int FMT_FP8 = 0, FMT_FP16 = 1, FMT_FP6 = 2, FMT_FP6_E3M2 = 3;     // FMT_FP6 is E2M3
+__host__ __device__ constexpr bool fmt_is_fp6(int fmt) { return fmt == FMT_FP6 || fmt == FMT_FP6_E3M2; }
 
 // ---- slice storage ---------------------------------------------------------------------------------------
 // One slice matrix (block t, slice p) of an operand is stored as [chunk kc][vector r][CHUNK_BYTES]:
@@ -44,7 +45,7 @@ constexpr int DELTA_IRREGULAR = -2147483647 - 1;
 
 struct Plan {
     int64_t m, n, k;
-    int fmt;              // FMT_FP8, FMT_FP16, FMT_FP6
+    int fmt;              // FMT_FP8, FMT_FP16, FMT_FP6, FMT_FP6_E3M2
     int epc;              // inner indices per chunk: 64 (FP8, FP6) or 32 (FP16)
     int row_bytes;        // bytes of one vector in one chunk: 64 (FP8, FP16) or 48 (FP6)
     int p_frac;           // a stored pair product is an integer multiple of 2^-p_frac: 2b, for FP6 (whose codes hold

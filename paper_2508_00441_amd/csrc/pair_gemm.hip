@@ -81,7 +81,8 @@ __device__ __forceinline__ void wait_and_barrier() {
 template <int FMT>
 __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
     constexpr bool FP16 = FMT == FMT_FP16;
-    constexpr bool FP6 = FMT == FMT_FP6;
+    constexpr bool FP6 = fmt_is_fp6(FMT);
+    constexpr int FP6_CODE = FMT == FMT_FP6_E3M2 ? 3 : 2;     // operand format field of the instruction: 2 = E2M3, 3 = E3M2
     constexpr int BK = FP6 ? CHUNK_BYTES_FP6 : CHUNK_BYTES;   // bytes of the inner dimension per vector and stage
     constexpr int OPERAND_BYTES = TILE * BK;          // one operand's share of a stage
     constexpr int STAGE_BYTES = 2 * OPERAND_BYTES;    // X tile + Y tile
@@ -257,7 +258,7 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 if constexpr (FP16) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf[fb][i], yf[fb][j], acc[i][j], 0, 0, 0);
-                else if constexpr (FP6) acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xf[fb][i], yf[fb][j], acc[i][j], 2, 2, 0, 0, 0, 0);
+                else if constexpr (FP6) acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xf[fb][i], yf[fb][j], acc[i][j], FP6_CODE, FP6_CODE, 0, 0, 0, 0);
                 else acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xf[fb][i], yf[fb][j], acc[i][j], 0, 0, 0, 0, 0, 0);
             }
     };
@@ -358,6 +359,7 @@ hipError_t launch_pair_gemm(const Plan& pl, const Operand& A, const Operand& B, 
     if (blocks > 0x7FFFFFFF || pl.chunks > 0x7FFFFFFF) return hipErrorInvalidValue;
     if (pl.fmt == FMT_FP16) hipLaunchKernelGGL((pair_gemm_kernel<FMT_FP16>), dim3((unsigned)blocks), dim3(256), 0, st, a);
     else if (pl.fmt == FMT_FP6) hipLaunchKernelGGL((pair_gemm_kernel<FMT_FP6>), dim3((unsigned)blocks), dim3(256), 0, st, a);
+    else if (pl.fmt == FMT_FP6_E3M2) hipLaunchKernelGGL((pair_gemm_kernel<FMT_FP6_E3M2>), dim3((unsigned)blocks), dim3(256), 0, st, a);
     else hipLaunchKernelGGL((pair_gemm_kernel<FMT_FP8>), dim3((unsigned)blocks), dim3(256), 0, st, a);
     return hipGetLastError();
 }

@@ -80,10 +80,18 @@ __device__ __forceinline__ uint32_t encode_e2m3(int q, int b) {
     return mag | (v < 0 ? 32u : 0u);
 }
 
+// FP6 E3M2 code of q * 2^-b (|q| <= 2^b, b <= 3): with q' = q * 2^(3-b) the value is q'/8; the codes (exponent field
+// << 2 | fraction) of the magnitudes 0 .. 8 are 0 (zero), 2 (subnormal 2/16), 4, 6, 8, 9, 10, 11, 12; bit 5 is the sign.
+__device__ __forceinline__ uint32_t encode_e3m2(int q, int b) {
+    const int v = q << (3 - b);
+    const uint32_t mag = (uint32_t)(v < 0 ? -v : v);
+    return (uint32_t)((0xCBA986420ull >> (4 * mag)) & 0xFull) | (v < 0 ? 32u : 0u);
+}
+
 template <int U, int TPR, int FMT>
 __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArgs a) {
     constexpr bool FP16 = FMT == FMT_FP16;
-    constexpr bool FP6 = FMT == FMT_FP6;
+    constexpr bool FP6 = fmt_is_fp6(FMT);
     constexpr int BLOCK = TPR < 256 ? 256 : TPR;
     constexpr int RPB = BLOCK / TPR;                  // vectors per workgroup
     constexpr int EPC = FP16 ? CHUNK_BYTES / 2 : CHUNK_BYTES;   // elements per chunk
@@ -247,7 +255,8 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
                 // 8-byte plane (see layout.hpp).  Written as one 32-bit and one 16-bit store, both naturally aligned.
                 uint64_t w48 = 0;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) w48 |= (uint64_t)encode_e2m3(qs[e], a.b) << (6 * e);
+                for (int e = 0; e < 8; ++e)
+                    w48 |= (uint64_t)(FMT == FMT_FP6_E3M2 ? encode_e3m2(qs[e], a.b) : encode_e2m3(qs[e], a.b)) << (6 * e);
                 if (ke < padded && a.slices != nullptr) {
                     const int64_t kc = ke / EPC;
                     const int o = (int)((ke % EPC) / 8), g = o >> 2, j = o & 3;
@@ -299,7 +308,7 @@ __global__ void __launch_bounds__(256) export_slices_kernel(const uint8_t* __res
                                                             int64_t k, int64_t kb, int64_t chunks, int s, void* out) {
     // plain layout: block t starts at s*rows*(t*kb) entries; inside, [p][row][kb_t]
     constexpr bool FP16 = FMT == FMT_FP16;
-    constexpr bool FP6 = FMT == FMT_FP6;
+    constexpr bool FP6 = fmt_is_fp6(FMT);
     constexpr int EPC = FP16 ? CHUNK_BYTES / 2 : CHUNK_BYTES;
     constexpr int ROWB = FP6 ? CHUNK_BYTES_FP6 : CHUNK_BYTES;
     const int64_t t = blockIdx.z, p = blockIdx.y;
@@ -353,6 +362,7 @@ hipError_t launch_split_cfg(const SplitArgs& a, int fmt, int64_t T, hipStream_t 
     dim3 grid((unsigned)((a.rows_pad + RPB - 1) / RPB), (unsigned)T);
     if (fmt == FMT_FP16) hipLaunchKernelGGL((split_kernel<U, TPR, FMT_FP16>), grid, dim3(BLOCK), 0, st, a);
     else if (fmt == FMT_FP6) hipLaunchKernelGGL((split_kernel<U, TPR, FMT_FP6>), grid, dim3(BLOCK), 0, st, a);
+    else if (fmt == FMT_FP6_E3M2) hipLaunchKernelGGL((split_kernel<U, TPR, FMT_FP6_E3M2>), grid, dim3(BLOCK), 0, st, a);
     else hipLaunchKernelGGL((split_kernel<U, TPR, FMT_FP8>), grid, dim3(BLOCK), 0, st, a);
     return hipGetLastError();
 }
@@ -407,7 +417,7 @@ hipError_t launch_export_slices(const Plan& pl, const Operand& op, void* out, hi
     dim3 grid(1024, (unsigned)pl.s, (unsigned)pl.T);
     if (pl.fmt == FMT_FP16)
         hipLaunchKernelGGL((export_slices_kernel<FMT_FP16>), grid, dim3(256), 0, st, op.slices, op.rows, op.rows_pad, pl.k, pl.kb, pl.chunks, pl.s, out);
-    else if (pl.fmt == FMT_FP6)
+    else if (fmt_is_fp6(pl.fmt))
         hipLaunchKernelGGL((export_slices_kernel<FMT_FP6>), grid, dim3(256), 0, st, op.slices, op.rows, op.rows_pad, pl.k, pl.kb, pl.chunks, pl.s, out);
     else
         hipLaunchKernelGGL((export_slices_kernel<FMT_FP8>), grid, dim3(256), 0, st, op.slices, op.rows, op.rows_pad, pl.k, pl.kb, pl.chunks, pl.s, out);

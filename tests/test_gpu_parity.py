@@ -84,6 +84,9 @@ SPLIT_CASES = [
     ("fp6", 40, 8192, 0, 16, 4.0),
     ("fp6", 9, 20000, 0, 5, 1.0),
     ("fp6", 17, 3, 0, 4, 1.0),
+    ("fp6_e3m2", 300, 1000, 0, 9, 4.0),
+    ("fp6_e3m2", 77, 1000, 384, 7, 2.0),
+    ("fp6_e3m2", 9, 20000, 0, 5, 1.0),
 ]
 
 
@@ -122,6 +125,9 @@ PRODUCT_CASES = [
     ("fp6", 300, 270, 520, 0, 6, 2.0),
     ("fp6", 100, 600, 1000, 384, 5, 4.0),
     ("fp6", 515, 260, 4096, 0, 3, 1.0),
+    ("fp6_e3m2", 300, 270, 520, 0, 6, 2.0),
+    ("fp6_e3m2", 100, 600, 1000, 384, 5, 4.0),
+    ("fp6_e3m2", 130, 70, 32768, 0, 3, 0.5),         # long inner dimension: sums up to 2^21 units
 ]
 
 
@@ -158,6 +164,8 @@ DGEMM_CASES = [
     ("fp6", 300, 270, 520, 0, 15, 4.0),
     ("fp6", 100, 600, 1000, 384, 12, 2.0),
     ("fp6", 513, 255, 2048, 0, 13, 1.0),
+    ("fp6_e3m2", 300, 270, 520, 0, 17, 2.0),
+    ("fp6_e3m2", 100, 600, 1000, 384, 15, 1.0),
 ]
 
 
@@ -357,7 +365,7 @@ def test_edge_cases_and_error_paths():
     assert lib.ozaki_dgemm(m, n, k, Ad, m - 1, Bd, k, Cd, m, 0, 4, 0, 0, check=False) == -5
     assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k - 1, Cd, m, 0, 4, 0, 0, check=False) == -7
     assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m - 1, 0, 4, 0, 0, check=False) == -9
-    assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 3, 4, 0, 0, check=False) == -10
+    assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 9, 4, 0, 0, check=False) == -10
     assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 0, 4, 0, 2, check=False) == -13
     assert lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, 0, 33, 0, 0, check=False) == lib.STATUS_INFEASIBLE
     # workspace too small
@@ -423,6 +431,28 @@ def test_products_at_the_edge_of_the_fp32_window():
     torch.cuda.synchronize()
     Pn = P.cpu().numpy()
     assert np.array_equal(np.abs(Pn[:, 2]), np.full((2, n, m), 1024.0, dtype=np.float32))   # pair (1,1): 2^24 * 2^-14
+    ws.close()
+
+
+@pytest.mark.parametrize("fmt,b", [("fp8", 4), ("fp6", 4), ("fp6_e3m2", 3)])
+def test_narrow_formats_at_the_edge_of_the_fp32_window(fmt, b):
+    """Every entry at the row maximum and the longest block the library takes: each product is +-k * 4^b units."""
+    m, n, k = 40, 24, 32768
+    A = np.ones((m, k))
+    B = np.ones((k, n))
+    B[:, ::2] = -1.0
+    Ad, Bd = _upload(A, B)
+    Cd = torch.zeros((n, m), dtype=torch.float64, device="cuda")
+    ws = device.Workspace.for_problem(m, n, k, FMT[fmt], 2, 0)
+    assert lib.ozaki_plan(k, FMT[fmt])[1] == b
+    for accum in (0, 1):
+        lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, FMT[fmt], 2, 0, accum)
+        torch.cuda.synchronize()
+        assert np.array_equal(device.from_device_colmajor(Cd), A @ B)
+    P = torch.zeros((1, 3, n, m), dtype=torch.float32, device="cuda")
+    lib.ozaki_pair_products(m, n, k, Ad, m, Bd, k, FMT[fmt], 2, 0, P)
+    torch.cuda.synchronize()
+    assert np.array_equal(np.abs(P.cpu().numpy()[0, 2]), np.full((n, m), float(k), dtype=np.float32))      # pair (1,1)
     ws.close()
 
 

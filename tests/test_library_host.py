@@ -39,7 +39,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_planner_matches_eq_1_to_3():
-    for fmt, fid in (("fp8", lib.SLICE_FP8_E4M3), ("fp16", lib.SLICE_FP16)):
+    for fmt, fid in (("fp8", lib.SLICE_FP8_E4M3), ("fp16", lib.SLICE_FP16), ("fp6", lib.SLICE_FP6_E2M3), ("fp6_e3m2", lib.SLICE_FP6_E3M2)):
         for k in [1, 2, 3, 8, 16, 17, 64, 65, 255, 256, 1024, 1025, 4096, 5000, 16384, 16385, 65536, 65537, 262144, 1 << 24]:
             p = oz.make_plan(k, fmt)
             assert lib.ozaki_plan(k, fid) == (p.rho, p.b), (fmt, k)

@@ -43,7 +43,7 @@ def test_emulated_accumulation_and_slicing_use_no_fp64(tmp_path):
     assert len(add_emu) == 1 and not re.search(r"\bv_\w*f64\w*", add_emu[0])
     split = _kernel_bodies("split.hip", tmp_path)
     sk = [b for n, b in split.items() if "split_kernel" in n]
-    assert len(sk) >= 21              # 7 launch shapes x 3 slice formats
+    assert len(sk) >= 28              # 7 launch shapes x 4 slice formats
     for body in sk:
         assert not re.search(r"\bv_\w*f64\w*", body), "FP64 instruction in a slicing kernel"
     gemm = _kernel_bodies("pair_gemm.hip", tmp_path)
