@@ -535,3 +535,36 @@ def test_dgemm_can_be_captured_in_a_hip_graph_and_replayed():
     lib.ozaki_set_stream(torch.cuda.current_stream().cuda_stream)
     assert lib.ozaki_last_device_status() == 0
     ws.close()
+
+
+def _random_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(count):
+        fmt = ["fp8", "fp16", "fp6", "fp6_e3m2"][int(rng.integers(0, 4))]
+        m, n = int(rng.integers(1, 400)), int(rng.integers(1, 400))
+        k = int(rng.integers(1, 3000))
+        kb = [0, int(rng.integers(1, k + 1)), int(rng.integers(1, 200))][int(rng.integers(0, 3))]
+        s = int(rng.integers(1, 11))
+        full = bool(rng.integers(0, 2)) and s <= 7
+        phi = float(rng.choice([0.5, 1.0, 3.0]))
+        accum = ["hw", "emu"][int(rng.integers(0, 2))]
+        cases.append((fmt, m, n, k, kb, s, full, phi, accum))
+    return cases
+
+
+@pytest.mark.parametrize("fmt,m,n,k,kb,s,full,phi,accum", _random_cases(24, seed=2025))
+def test_random_shapes_and_parameters_match_oracle(fmt, m, n, k, kb, s, full, phi, accum):
+    """Seeded random problem shapes, block lengths (any value, also shorter than a chunk), slice counts, pair sets and
+    formats: C bit-identical to the oracle."""
+    A, B = inputs.phi_pair(m, n, k, phi, seed=m * 7 + n * 3 + k)
+    Ad, Bd = _upload(A, B)
+    s_arg = s | lib.PAIRS_ALL if full else s
+    Cd = torch.full((n, m), float("nan"), dtype=torch.float64, device="cuda")
+    ws = device.Workspace.for_problem(m, n, k, FMT[fmt], s_arg, kb)
+    lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, FMT[fmt], s_arg, kb, ACC[accum])
+    assert lib.ozaki_last_device_status() == 0
+    C = device.from_device_colmajor(Cd)
+    ws.close()
+    Cref = oz.ozaki_dgemm(A, B, fmt, s, kb, mode="full" if full else "triangle")
+    assert np.array_equal(C.view(np.uint64), Cref.view(np.uint64))
