@@ -118,18 +118,6 @@ OZAKI_HD uint64_t fp64_mul_emulated(uint64_t a, uint64_t b) {
     return sign | r;
 }
 
-// Exact conversion of a normal (or zero) FP32 bit pattern times 2^e2 to FP64 bits, integer-only.
-// Returns 0 for a zero input.  The caller guarantees the result stays in the normal FP64 range,
-// except that a too small result is flushed to zero.
-OZAKI_HD uint64_t fp32_bits_scaled_to_fp64(uint32_t f, int e2) {
-    if ((f << 1) == 0) return 0;
-    uint64_t sign = (uint64_t)(f >> 31) << 63;
-    int e = (int)((f >> 23) & 0xFF) - 127 + 1023 + e2;
-    if (e <= 0) return 0;
-    if (e >= 2047) return sign | F64_INF;
-    return sign | ((uint64_t)e << 52) | ((uint64_t)(f & 0x7FFFFFu) << 29);
-}
-
 // n * 2^e2 as FP64 bits for a 32-bit integer n (exact), integer-only; flushed / saturated outside the normal range.
 OZAKI_HD uint64_t int32_scaled_to_fp64(int n, int e2) {
     if (n == 0) return 0;

@@ -12,9 +12,6 @@ void host_fp64_mul_emulated(const uint64_t* a, const uint64_t* b, uint64_t* out,
 void host_mul_64x64_128(const uint64_t* a, const uint64_t* b, uint64_t* hi, uint64_t* lo, size_t n) {
     for (size_t i = 0; i < n; ++i) ozaki::mul_64x64_128(a[i], b[i], hi[i], lo[i]);
 }
-void host_fp32_scaled_to_fp64(const uint32_t* f, const int* e2, uint64_t* out, size_t n) {
-    for (size_t i = 0; i < n; ++i) out[i] = ozaki::fp32_bits_scaled_to_fp64(f[i], e2[i]);
-}
 void host_int32_scaled_to_fp64(const int* v, const int* e2, uint64_t* out, size_t n) {
     for (size_t i = 0; i < n; ++i) out[i] = ozaki::int32_scaled_to_fp64(v[i], e2[i]);
 }

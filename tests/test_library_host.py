@@ -166,22 +166,16 @@ def test_product_fp64_mul_emulation_on_host_equals_fpu(host_emu):
         assert (h << 64) | l == xi * yi
 
 
-def test_product_fp32_to_fp64_scaling_on_host(host_emu):
+def test_product_power_of_two_scaling_on_host(host_emu):
     rng = np.random.default_rng(6)
     n = 500_000
-    f = np.ldexp(rng.integers(-(1 << 24), (1 << 24) + 1, n).astype(np.float32), -8)
+    f = np.ldexp(rng.integers(-(1 << 24), (1 << 24) + 1, n).astype(np.float64), -8)
+    x = np.ldexp(f, rng.integers(-300, 300, n))
     e2 = rng.integers(-300, 300, n).astype(np.int32)
     out = np.empty(n, dtype=np.uint64)
-    host_emu.host_fp32_scaled_to_fp64(f.ctypes.data_as(ctypes.c_void_p), e2.ctypes.data_as(ctypes.c_void_p),
-                                      out.ctypes.data_as(ctypes.c_void_p), ctypes.c_size_t(n))
-    want = np.ldexp(f.astype(np.float64), e2)
-    want = np.where(f == 0, 0.0, want)
-    assert np.array_equal(out, want.view(np.uint64))
-    x = want
-    out2 = np.empty(n, dtype=np.uint64)
     host_emu.host_fp64_scale_pow2(x.ctypes.data_as(ctypes.c_void_p), e2.ctypes.data_as(ctypes.c_void_p),
-                                  out2.ctypes.data_as(ctypes.c_void_p), ctypes.c_size_t(n))
-    assert np.array_equal(out2, np.ldexp(x, e2).view(np.uint64))
+                                  out.ctypes.data_as(ctypes.c_void_p), ctypes.c_size_t(n))
+    assert np.array_equal(out, np.ldexp(x, e2).view(np.uint64))
 
 
 def test_product_integer_conversions_on_host(host_emu):
