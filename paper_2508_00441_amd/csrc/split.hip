@@ -214,7 +214,7 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
                         T <<= (ef - unit);
                         pk[i] = ACTIVE;
                         active = true;
-                    } else if (unit - ef + F <= 53) {
+                    } else if (FP16 && unit - ef + F <= 53) {       // only FP16 has slices of more than 7 bits
                         // Wide slices only (b >= 8, fewer than 53 fraction bits): the element reaches the unit but its
                         // low bits do not fit the fixed-point form yet.  Round its integer form tv * 2^E directly, by
                         // sh = unit - E bits, and let the remainder wait on as a dormant element with the same E.
