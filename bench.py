@@ -186,6 +186,18 @@ def main():
         "mfma_frac_of_total_time": pairs * flop / sec_per_step / 1e12 / peak,
     }
     if not args.no_cpu_baseline:
+        # context: the GPU's native FP64 GEMM on the same operands (C^T = B^T A^T in torch's row-major view)
+        try:
+            ref = torch.matmul(Bd, Ad)
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            for _ in range(3):
+                ref = torch.matmul(Bd, Ad)
+            torch.cuda.synchronize()
+            out["native_fp64_dgemm_tflops"] = flop / ((time.perf_counter() - t2) / 3) / 1e12
+            del ref
+        except RuntimeError:                     # no room left beside the workspace
+            out["native_fp64_dgemm_tflops"] = None
         sample = args.sample or {256: 256, 1024: 2048, 4096: 2048, 8192: 1536, 16384: 1280, 65536: 512}.get(k, 256)
         out.update(cpu_baseline_leg(cfg, s, A, B, Cd, sample))
     ws.close()
