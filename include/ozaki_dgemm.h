@@ -133,7 +133,7 @@ int ozaki_set_stream(void* hip_stream);
 /*
  * Workspace (Section 5.1: work memory is allocated once, outside the timed region).
  *   ozaki_workspace_bytes      size that lets ozaki_dgemm keep all s(s+1)/2 pair products of one block
- *                              resident (capped at 64 GiB of products; more pairs are then processed in
+ *                              resident (capped at 160 GiB of products; more pairs are then processed in
  *                              several passes).  0 if the arguments are invalid or infeasible.
  *   ozaki_workspace_min_bytes  smallest size ozaki_dgemm accepts (the s products of the longest anti-diagonal
  *                              resident at a time).

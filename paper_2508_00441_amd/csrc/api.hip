@@ -28,7 +28,7 @@ State g;
 
 constexpr size_t ALIGN = 256;
 constexpr size_t FLAG_BYTES = 256;
-constexpr size_t P_BUDGET = (size_t)64 << 30;
+constexpr size_t P_BUDGET = (size_t)160 << 30;        // resident pair products: well inside the 288 GB of one GPU
 size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 int fail_hip(hipError_t e) {

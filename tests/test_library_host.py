@@ -62,8 +62,8 @@ def test_workspace_sizes():
     assert full >= 136 * pair + slices + 8192 * 8192 * 8
     assert slices + 8192 * 8192 * 8 + pair < mini < full
     # more pairs than the resident-product budget: capped, with room for the running FP64 sum
-    big = lib.ozaki_workspace_bytes(16384, 16384, 16384, 0, 13, 0)
-    assert big < (64 << 30) + 2 * 13 * 16384 * 16384 + 3 * 16384 * 16384 * 8 + (1 << 20)
+    big = lib.ozaki_workspace_bytes(32768, 32768, 16384, 0, 13, 0)          # 91 products of 4 GiB
+    assert big < (160 << 30) + 2 * 13 * 32768 * 16384 + 3 * 32768 * 32768 * 8 + (1 << 20)
     assert lib.ozaki_workspace_bytes(16, 16, 16, 5, 4, 0) == 0          # bad format
     assert lib.ozaki_workspace_bytes(16, 16, 1 << 20, 0, 4, 0) == 0     # block longer than the library supports
     assert lib.ozaki_workspace_bytes(16, 16, 1 << 20, 0, 4, 8192) > 0
