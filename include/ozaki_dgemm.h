@@ -127,6 +127,15 @@ int ozaki_dgemm_scaled(int64_t m, int64_t n, int64_t k, double alpha,
                        int slice_format, int num_slices, int64_t k_block, int accum_mode);
 size_t ozaki_workspace_bytes_scaled(int64_t m, int64_t n, int64_t k, int slice_format, int num_slices, int64_t k_block);
 
+/*
+ * ozaki_suggest_k_block -- a block length for the inner dimension k (Section 4.3 leaves the choice to the user).
+ * A heuristic from measurements on MI355X, not part of the method: FP8 / FP6 slices keep b = 4 up to k = 65536, so
+ * they are blocked only as far as the library's OZAKI_MAX_K_BLOCK requires; FP16 gains a magnitude bit per factor 4
+ * in the block length, and 4096 (b = 6) was the fastest block at k = 16384 (the paper reports the same optimum on
+ * its GPU).  Returns the suggested k_block (0 = no blocking), or a negative argument index.  HOST call.
+ */
+int64_t ozaki_suggest_k_block(int64_t k, int slice_format);
+
 /* Stream (a hipStream_t passed as void*; NULL = the null stream) used by all later calls. HOST call. */
 int ozaki_set_stream(void* hip_stream);
 

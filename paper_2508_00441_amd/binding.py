@@ -37,6 +37,7 @@ SIGNATURES = {
                                   _i64, _int]),
     "ozaki_workspace_bytes_scaled": (_sz, [_i64, _i64, _i64, _int, _int, _i64]),
     "ozaki_count_slices": (_int, [_int, _i64, _i64, _vp, _i64, _int, _i64, ctypes.POINTER(ctypes.c_int)]),
+    "ozaki_suggest_k_block": (_i64, [_i64, _int]),
     "ozaki_set_stream": (_int, [_vp]),
     "ozaki_workspace_bytes": (_sz, [_i64, _i64, _i64, _int, _int, _i64]),
     "ozaki_workspace_min_bytes": (_sz, [_i64, _i64, _i64, _int, _int, _i64]),
@@ -102,6 +103,13 @@ def ozaki_plan(k_block: int, slice_format: int) -> Tuple[int, int]:
 
 def ozaki_set_stream(stream_handle: int) -> None:
     _check(load().ozaki_set_stream(stream_handle), "ozaki_set_stream")
+
+
+def ozaki_suggest_k_block(k, slice_format) -> int:
+    r = int(load().ozaki_suggest_k_block(k, slice_format))
+    if r < 0:
+        raise OzakiError(r, "ozaki_suggest_k_block")
+    return r
 
 
 def ozaki_workspace_bytes(m, n, k, slice_format, num_slices, k_block) -> int:

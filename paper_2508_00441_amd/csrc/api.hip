@@ -278,6 +278,13 @@ int ozaki_plan(int64_t k_block, int slice_format, int* rho_out, int* bits_out) {
     return 0;
 }
 
+int64_t ozaki_suggest_k_block(int64_t k, int slice_format) {
+    if (k < 0) return -1;
+    if (slice_format < OZAKI_SLICE_FP8_E4M3 || slice_format > OZAKI_SLICE_FP6_E3M2) return -2;
+    if (slice_format == OZAKI_SLICE_FP16) return k > 4096 ? 4096 : 0;
+    return k > MAX_K_BLOCK ? MAX_K_BLOCK : 0;
+}
+
 int ozaki_set_stream(void* hip_stream) {
     g.stream = reinterpret_cast<hipStream_t>(hip_stream);
     return 0;

@@ -54,6 +54,18 @@ def test_planner_matches_eq_1_to_3():
     assert e.value.status == -2
 
 
+def test_k_block_suggestion_keeps_the_plan_feasible():
+    """A heuristic (parity unpinned); what is checked: the suggested block is accepted by the planner."""
+    for fid in (lib.SLICE_FP8_E4M3, lib.SLICE_FP16, lib.SLICE_FP6_E2M3, lib.SLICE_FP6_E3M2):
+        for k in (1, 100, 4096, 4097, 16384, 32768, 32769, 1 << 20):
+            kb = lib.ozaki_suggest_k_block(k, fid)
+            assert 0 <= kb <= lib.MAX_K_BLOCK and (kb or k) <= lib.MAX_K_BLOCK
+            assert lib.ozaki_workspace_bytes(64, 64, k, fid, 4, kb) > 0
+    assert lib.ozaki_suggest_k_block(16384, lib.SLICE_FP16) == 4096 and lib.ozaki_suggest_k_block(16384, lib.SLICE_FP8_E4M3) == 0
+    with pytest.raises(lib.OzakiError):
+        lib.ozaki_suggest_k_block(16, 9)
+
+
 def test_workspace_sizes():
     full = lib.ozaki_workspace_bytes(8192, 8192, 8192, 0, 16, 0)
     mini = lib.ozaki_workspace_min_bytes(8192, 8192, 8192, 0, 16, 0)
