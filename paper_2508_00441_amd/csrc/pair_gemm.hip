@@ -256,7 +256,8 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int jj = 0; jj < 4; ++jj) {
+                const int j = (i & 1) ? 3 - jj : jj;      // boustrophedon: consecutive MFMAs differ in one operand only
                 if constexpr (FP16) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf[fb][i], yf[fb][j], acc[i][j], 0, 0, 0);
                 else if constexpr (FP6) acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xf[fb][i], yf[fb][j], acc[i][j], FP6_CODE, FP6_CODE, 0, 0, 0, 0);
                 else acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xf[fb][i], yf[fb][j], acc[i][j], 0, 0, 0, 0, 0, 0);
