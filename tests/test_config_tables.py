@@ -32,3 +32,12 @@ def test_paper_workload_uses_the_slice_counts_of_table_2(golden_dir):
         col = 0 if cfg["fmt"] == "fp16" else 2                  # FP16 / FP8 E4M3 with FP32 accumulation
         assert s * s == int(table[kb][col]), name
         assert cfg["pairs"] == "all" and cfg["dist"] == "u110" and cfg["m"] == cfg["n"] == cfg["k"]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU per box: the benchmark says so and exits instead of pretending to scale."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert res.returncode != 0 and "one GPU" in res.stderr and res.stdout.strip() == ""
