@@ -122,10 +122,20 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
     __syncthreads();
     const int n_runs = n_entries;
 
+    // Integer-only variant: the sum lives in a RoundedSum, which adds exactly in 64-bit integers for as long as no
+    // rounding can occur and with the emulated FP64 addition from then on.
+    RoundedSum E[4];
+    if constexpr (EMU) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            if (a.read_S) E[r].start_at((uint64_t)S[r]);
+            else E[r].start_at_zero();
+        }
+    }
     auto add_run = [&](int r, int run_sum, int run_e) {
         if (run_sum == 0) return;                                     // adding an exact zero changes nothing
         if constexpr (EMU) {
-            S[r] = (acc_t)fp64_add_emulated((uint64_t)S[r], int32_scaled_to_fp64(run_sum, run_e - a.two_b));
+            E[r].add(run_sum, run_e - a.two_b);
         } else {
             S[r] = (acc_t)((double)S[r] + ldexp((double)run_sum, run_e - a.two_b));
         }
@@ -160,17 +170,18 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
     // four loads in flight per thread
     if (n_runs > 0) {
         uint4 v0 = load_run(0), v1 = load_run(1), v2 = load_run(2), v3 = load_run(3);
-        for (int i = 0; i < n_runs; i += 4) {
-            const uint4 w0 = v0, w1 = v1, w2 = v2, w3 = v3;
-            v0 = load_run(i + 4); v1 = load_run(i + 5); v2 = load_run(i + 6); v3 = load_run(i + 7);
-            process(entries[i], w0);
-            if (i + 1 < n_runs) process(entries[i + 1], w1);
-            if (i + 2 < n_runs) process(entries[i + 2], w2);
-            if (i + 3 < n_runs) process(entries[i + 3], w3);
+        for (int i = 0; i < n_runs; ++i) {
+            const uint4 w = v0;
+            v0 = v1; v1 = v2; v2 = v3;
+            v3 = load_run(i + 4);
+            process(entries[i], w);
         }
     }
 #pragma unroll
-    for (int r = 0; r < 4; ++r) add_run(r, run_sum[r], run_e[r]);
+    for (int r = 0; r < 4; ++r) {
+        add_run(r, run_sum[r], run_e[r]);
+        if constexpr (EMU) S[r] = (acc_t)E[r].value();
+    }
 
     if (a.write_S) {
 #pragma unroll

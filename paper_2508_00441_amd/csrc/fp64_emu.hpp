@@ -118,17 +118,51 @@ OZAKI_HD uint64_t fp64_mul_emulated(uint64_t a, uint64_t b) {
     return sign | r;
 }
 
-// n * 2^e2 as FP64 bits for a 32-bit integer n (exact), integer-only; flushed / saturated outside the normal range.
-OZAKI_HD uint64_t int32_scaled_to_fp64(int n, int e2) {
+// n * 2^e2 as FP64 bits for an integer |n| < 2^53 (exact), integer-only; flushed / saturated outside the normal range.
+OZAKI_HD uint64_t int53_scaled_to_fp64(int64_t n, int e2) {
     if (n == 0) return 0;
     const uint64_t sign = n < 0 ? F64_SIGN : 0;
-    const uint64_t a = (uint64_t)(n < 0 ? -(int64_t)n : (int64_t)n);
+    const uint64_t a = (uint64_t)(n < 0 ? -n : n);
     const int top = 63 - clz64(a);                           // position of the leading one
     const int e = 1023 + top + e2;
     if (e <= 0) return sign;
     if (e >= 2047) return sign | F64_INF;
     return sign | ((uint64_t)e << 52) | ((a << (52 - top)) & F64_FRAC);
 }
+
+// A running FP64 sum of terms v * 2^e2 (v a 32-bit integer), each addition rounded to nearest even.  As long as the sum
+// and the next term fit together into 53 bits (both below 2^52 in units of the smaller of their two scales) the
+// rounded addition is exact, so the sum is held as a 64-bit integer x * 2^ex and an addition is a shift and an
+// integer add; the first addition that may round turns the sum into FP64 bits once and fp64_add_emulated takes over.
+// Bit for bit the chain of rounded additions, inside the normal range.
+struct RoundedSum {
+    uint64_t w;         // the sum: the integer x of x * 2^ex (two's complement) while exact, FP64 bits afterwards
+    int ex;             // NOT_EXACT once the sum is held as FP64 bits
+    static constexpr int NOT_EXACT = -0x40000000;
+
+    OZAKI_HD bool exact() const { return ex != NOT_EXACT; }
+    OZAKI_HD void start_at_zero() { w = 0; ex = 0; }
+    OZAKI_HD void start_at(uint64_t fp64_bits) { w = fp64_bits; ex = NOT_EXACT; }
+    OZAKI_HD void add(int v, int e2) {
+        if (v == 0) return;                                     // adding an exact zero changes nothing
+        if (exact()) {
+            const int64_t x = (int64_t)w;
+            if (x == 0) { w = (uint64_t)(int64_t)v; ex = e2; return; }
+            const int lo = ex < e2 ? ex : e2, sx = ex - lo, sv = e2 - lo;
+            const uint64_t ax = (uint64_t)(x < 0 ? -x : x);
+            const uint64_t av = (uint64_t)(v < 0 ? -(int64_t)v : (int64_t)v);
+            if (64 - clz64(ax) + sx <= 52 && 64 - clz64(av) + sv <= 52) {
+                w = (w << sx) + ((uint64_t)(int64_t)v << sv);
+                ex = lo;
+                return;
+            }
+            w = int53_scaled_to_fp64(x, ex);
+            ex = NOT_EXACT;
+        }
+        w = fp64_add_emulated(w, int53_scaled_to_fp64(v, e2));
+    }
+    OZAKI_HD uint64_t value() const { return exact() ? int53_scaled_to_fp64((int64_t)w, ex) : w; }
+};
 
 // x * 2^e2 on FP64 bits (zeros stay zeros; the result is flushed / saturated outside the normal range).
 OZAKI_HD uint64_t fp64_scale_pow2_emulated(uint64_t x, int e2) {

@@ -12,8 +12,23 @@ void host_fp64_mul_emulated(const uint64_t* a, const uint64_t* b, uint64_t* out,
 void host_mul_64x64_128(const uint64_t* a, const uint64_t* b, uint64_t* hi, uint64_t* lo, size_t n) {
     for (size_t i = 0; i < n; ++i) ozaki::mul_64x64_128(a[i], b[i], hi[i], lo[i]);
 }
-void host_int32_scaled_to_fp64(const int* v, const int* e2, uint64_t* out, size_t n) {
-    for (size_t i = 0; i < n; ++i) out[i] = ozaki::int32_scaled_to_fp64(v[i], e2[i]);
+void host_int53_scaled_to_fp64(const int64_t* v, const int* e2, uint64_t* out, size_t n) {
+    for (size_t i = 0; i < n; ++i) out[i] = ozaki::int53_scaled_to_fp64(v[i], e2[i]);
+}
+// n_seq sequences of len terms v * 2^e2 each, summed front to back with ozaki::RoundedSum; start[i] != 0 begins
+// from those FP64 bits instead of zero.  exact_adds counts the additions taken in the integer phase.
+void host_rounded_sum(const int* v, const int* e2, const uint64_t* start, uint64_t* out, long long* exact_adds, size_t n_seq, size_t len) {
+    long long cnt = 0;
+    for (size_t i = 0; i < n_seq; ++i) {
+        ozaki::RoundedSum s;
+        if (start[i]) s.start_at(start[i]); else s.start_at_zero();
+        for (size_t j = 0; j < len; ++j) {
+            s.add(v[i * len + j], e2[i * len + j]);
+            cnt += s.exact();
+        }
+        out[i] = s.value();
+    }
+    *exact_adds = cnt;
 }
 void host_fp64_scale_pow2(const uint64_t* x, const int* e2, uint64_t* out, size_t n) {
     for (size_t i = 0; i < n; ++i) out[i] = ozaki::fp64_scale_pow2_emulated(x[i], e2[i]);

@@ -193,12 +193,47 @@ def test_product_power_of_two_scaling_on_host(host_emu):
 def test_product_integer_conversions_on_host(host_emu):
     rng = np.random.default_rng(8)
     n = 400_000
-    v = rng.integers(-(1 << 31) + 1, 1 << 31, n).astype(np.int32)
-    v[:4] = [0, 1, -1, (1 << 31) - 1]
+    bits = rng.integers(1, 54, n)                                   # all magnitudes below 2^53, every bit length
+    v = (rng.integers(0, 1 << 53, n) >> (53 - bits)) * rng.choice([-1, 1], n)
+    v[:6] = [0, 1, -1, (1 << 31) - 1, (1 << 53) - 1, -(1 << 53) + 1]
+    v = v.astype(np.int64)
     e2 = rng.integers(-300, 300, n).astype(np.int32)
     out = np.empty(n, dtype=np.uint64)
-    host_emu.host_int32_scaled_to_fp64(v.ctypes.data_as(ctypes.c_void_p), e2.ctypes.data_as(ctypes.c_void_p),
+    host_emu.host_int53_scaled_to_fp64(v.ctypes.data_as(ctypes.c_void_p), e2.ctypes.data_as(ctypes.c_void_p),
                                        out.ctypes.data_as(ctypes.c_void_p), ctypes.c_size_t(n))
     want = np.ldexp(v.astype(np.float64), e2)
     assert np.array_equal(out, want.view(np.uint64))
 
+
+
+def test_product_rounded_sum_on_host_equals_chain_of_fpu_additions(host_emu):
+    """The accumulation kernel's running sum (integer while no rounding can occur, emulated FP64 afterwards) must
+    give the bits of the plain chain of rounded FP64 additions, for the exponent patterns the method produces
+    (terms about 2^b apart, least significant first) and for arbitrary ones (cancellation, reordering, ties)."""
+    rng = np.random.default_rng(12)
+    n_seq, length = 60_000, 18
+    v = rng.integers(-(1 << 29), (1 << 29) + 1, (n_seq, length)).astype(np.int32)
+    v[rng.random((n_seq, length)) < 0.1] = 0
+    small = rng.random((n_seq, length)) < 0.3
+    v[small] = rng.integers(-40, 41, int(small.sum()))
+    e2 = np.empty((n_seq, length), dtype=np.int32)
+    third = n_seq // 3
+    e2[:third] = -100 + np.cumsum(rng.integers(3, 7, (third, length)), axis=1)                 # ascending, like anti-diagonals
+    e2[third:2 * third] = rng.integers(-60, 60, (third, length))                              # unordered
+    e2[2 * third:] = rng.integers(-3, 4, (n_seq - 2 * third, length))                         # close: long integer phases
+    v[2 * third:2 * third + 2000, 1] = -v[2 * third:2 * third + 2000, 0]                      # exact cancellation ...
+    e2[2 * third:2 * third + 2000, 1] = e2[2 * third:2 * third + 2000, 0]                     # ... back to zero
+    start = np.zeros(n_seq, dtype=np.float64)
+    start[::7] = _rnd(rng, start[::7].size, -40, 40)                                          # continued block sums
+    out = np.empty(n_seq, dtype=np.uint64)
+    exact_adds = ctypes.c_longlong(0)
+    v, e2 = np.ascontiguousarray(v), np.ascontiguousarray(e2)
+    host_emu.host_rounded_sum(v.ctypes.data_as(ctypes.c_void_p), e2.ctypes.data_as(ctypes.c_void_p), start.ctypes.data_as(ctypes.c_void_p),
+                              out.ctypes.data_as(ctypes.c_void_p), ctypes.byref(exact_adds), ctypes.c_size_t(n_seq), ctypes.c_size_t(length))
+    want = start.copy()
+    for j in range(length):
+        want = want + np.ldexp(v[:, j].astype(np.float64), e2[:, j])
+    assert np.array_equal(out, want.view(np.uint64))
+    # both phases are exercised: a good share of the additions in the integer phase, a good share after it
+    share = exact_adds.value / (n_seq * length)
+    assert 0.2 < share < 0.8
