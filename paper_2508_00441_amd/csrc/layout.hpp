@@ -59,6 +59,7 @@ struct Plan {
     int full;             // 1: all s*s pairs, 0: the pairs with p + q <= s + 1
     int npairs;           // s(s+1)/2 or s*s
     int run_limit;        // floor(2^24 / (kb * 4^b)): equal-scale pair products that may be summed exactly in FP32
+    int group_len;        // pairs per group of the GEMM kernel, <= run_limit (PairOrder::run_limit of the launches)
     int64_t tiles_m, tiles_n;
     int64_t m_pad, n_pad;
 };
@@ -66,14 +67,14 @@ struct Plan {
 // The slice pairs (p, q), 1-based, and their accumulation order: anti-diagonals g = p + q from the least
 // significant (largest g) down to g = 2, p ascending inside one.  Triangle mode uses the pairs with p + q <= s + 1,
 // full mode all s * s.  Consecutive pairs of an anti-diagonal with equal scale are summed exactly before the FP64
-// addition; the matrix unit can do that for at most run_limit pairs (the exact FP32 window), so every anti-diagonal is
-// cut into groups of at most run_limit consecutive pairs, the unit of work of the GEMM kernel; pairs are numbered
-// z = 0, 1, ... in this order.  Everything below is a closed form of (s, full, run_limit), evaluated on the host and
-// in the kernels.
+// addition; the matrix unit can do that for as many pairs as fit the exact FP32 window (Plan::run_limit), so every
+// anti-diagonal is cut into groups of at most run_limit consecutive pairs (Plan::group_len, never more than the
+// window), the unit of work of the GEMM kernel; pairs are numbered z = 0, 1, ... in this order.  Everything below
+// is a closed form of (s, full, run_limit), evaluated on the host and in the kernels.
 struct PairOrder {
     int s;
     int full;
-    int run_limit;
+    int run_limit;        // pairs per group
 };
 __host__ __device__ inline int order_top_diag(const PairOrder& o) { return o.full ? 2 * o.s : o.s + 1; }
 __host__ __device__ inline int diag_first_p(const PairOrder& o, int g) { return g - o.s > 1 ? g - o.s : 1; }
@@ -82,6 +83,11 @@ __host__ __device__ inline int diag_len(const PairOrder& o, int g) {
     return hi - diag_first_p(o, g) + 1;
 }
 __host__ __device__ inline int diag_groups(const PairOrder& o, int g) { return (diag_len(o, g) + o.run_limit - 1) / o.run_limit; }
+__host__ __device__ inline int order_num_groups(const PairOrder& o) {
+    int n = 0;
+    for (int g = order_top_diag(o); g >= 2; --g) n += diag_groups(o, g);
+    return n;
+}
 __host__ __device__ inline int order_num_pairs(const PairOrder& o) { return o.full ? o.s * o.s : o.s * (o.s + 1) / 2; }
 
 // A pass of the accumulation: the anti-diagonals g_hi, g_hi - 1, ..., g_lo; its pair products occupy the slots
