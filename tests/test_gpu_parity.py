@@ -166,6 +166,10 @@ DGEMM_CASES = [
     ("fp6", 513, 255, 2048, 0, 13, 1.0),
     ("fp6_e3m2", 300, 270, 520, 0, 17, 2.0),
     ("fp6_e3m2", 100, 600, 1000, 384, 15, 1.0),
+    # few tiles, long k (64 or more stages per pair): the plan shortens the GEMM kernel's groups
+    ("fp8", 300, 270, 5000, 0, 11, 1.0),
+    ("fp6", 260, 500, 9000, 4608, 11, 1.0),
+    ("fp16", 300, 130, 4100, 2050, 8, 1.0),
 ]
 
 
