@@ -386,6 +386,12 @@ hipError_t launch_split(const double* X, int64_t ldv, const Plan& pl, const Oper
     // sixteen elements per thread (U = 2) is the measured optimum: more elements per thread cost registers and with
     // them the occupancy that hides the latency of the dependent integer chains (64 per thread: one wave per SIMD)
     if (octets <= 64) return launch_split_cfg<1, 64>(a, fmt, pl.T, st);
+    // a small problem (few vectors) is bound by the length of a thread's dependent chain, not by throughput: eight
+    // elements per thread there (1024 x 1024: 0.080 -> 0.065 ms for both operands; no gain from 2048 vectors on)
+    if (op.rows_pad * pl.T <= 1024) {
+        if (octets <= 128) return launch_split_cfg<1, 128>(a, fmt, pl.T, st);
+        if (octets <= 256) return launch_split_cfg<1, 256>(a, fmt, pl.T, st);
+    }
     if (octets <= 128) return launch_split_cfg<2, 64>(a, fmt, pl.T, st);
     if (octets <= 256) return launch_split_cfg<2, 128>(a, fmt, pl.T, st);
     if (octets <= 512) return launch_split_cfg<2, 256>(a, fmt, pl.T, st);
