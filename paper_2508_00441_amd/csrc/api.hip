@@ -200,15 +200,11 @@ struct Phase {
 // split both operands of the plan into the carved buffers
 int run_split(const Plan& pl, const Carve& c, const double* A, int64_t lda, const double* B, int64_t ldb, bool do_a, bool do_b) {
     Phase ph(0);
-    if (do_a && pl.m > 0) {
-        HIP_TRY(launch_transpose(A, lda, pl.m, pl.k, c.At, g.stream));
-        HIP_TRY(launch_split(c.At, pl.k, pl, c.A, c.flags, g.stream));
-        HIP_TRY(launch_deltas(pl, c.A, g.stream));
-    }
-    if (do_b && pl.n > 0) {
-        HIP_TRY(launch_split(B, ldb, pl, c.B, c.flags, g.stream));
-        HIP_TRY(launch_deltas(pl, c.B, g.stream));
-    }
+    const bool a_on = do_a && pl.m > 0, b_on = do_b && pl.n > 0;
+    if (a_on) HIP_TRY(launch_transpose(A, lda, pl.m, pl.k, c.At, g.stream));
+    // both operands in one launch each: on a small problem neither fills the chip alone
+    HIP_TRY(launch_split(c.At, pl.k, a_on ? &c.A : nullptr, B, ldb, b_on ? &c.B : nullptr, pl, c.flags, g.stream));
+    HIP_TRY(launch_deltas(pl, a_on ? &c.A : nullptr, b_on ? &c.B : nullptr, g.stream));
     return 0;
 }
 

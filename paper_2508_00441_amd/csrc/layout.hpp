@@ -147,8 +147,10 @@ __host__ __device__ inline void acc_order_to_mn(int idx, int& m_in_tile, int& n_
 // ---- launchers (each enqueues on `st` and returns the launch status) ----------------------------------------
 hipError_t launch_transpose(const double* A, int64_t lda, int64_t m, int64_t k, double* At, hipStream_t st);
 
-// Vectors are contiguous: vector r starts at X + r*ldv and has k entries.  Writes the internal layout.
-hipError_t launch_split(const double* X, int64_t ldv, const Plan& pl, const Operand& op, int* flags, hipStream_t st);
+// Vectors are contiguous: vector r of an operand starts at X + r*ldv and has k entries.  Writes the internal layout of
+// up to two operands in one launch (a null Operand, or one without vectors, is skipped).
+hipError_t launch_split(const double* X0, int64_t ldv0, const Operand* op0, const double* X1, int64_t ldv1, const Operand* op1,
+                        const Plan& pl, int* flags, hipStream_t st);
 
 // Slices until every remainder is zero (paragraph before Eq. 4): atomicMax of the per-vector count into flags[1]
 // (which the caller has cleared); MAX_SLICES + 1 means that MAX_SLICES slices do not exhaust some vector.
@@ -157,8 +159,8 @@ hipError_t launch_count_slices(const double* X, int64_t ldv, const Plan& pl, int
 // Internal layout -> plain vector-major codes (verification export).
 hipError_t launch_export_slices(const Plan& pl, const Operand& op, void* out, hipStream_t st);
 
-// Fills Operand::deltas from Operand::exps.
-hipError_t launch_deltas(const Plan& pl, const Operand& op, hipStream_t st);
+// Fills Operand::deltas from Operand::exps, for up to two operands in one launch.
+hipError_t launch_deltas(const Plan& pl, const Operand* op0, const Operand* op1, hipStream_t st);
 
 // Products of the pairs of pass `ps` of block t into P ([ps.npairs][tiles_n][tiles_m][TILE_ELEMS] floats).  With
 // allow_chain, consecutive pairs of a group that are linked for a tile (pair_linked) form a run whose exact sum is

@@ -18,6 +18,8 @@
 //
 // A vector is held in the registers of TPR threads (8*U consecutive elements per thread in U groups of
 // eight) for all s slices, so HBM sees each input element once and each slice code once.
+#include <string.h>
+
 #include "layout.hpp"
 
 namespace ozaki {
@@ -40,16 +42,24 @@ __global__ void __launch_bounds__(256) transpose_kernel(const double* __restrict
     }
 }
 
-struct SplitArgs {
+// One operand of a split launch.
+struct SplitVectors {
     const double* X;       // vector r starts at X + r*ldv
     int64_t ldv;
     int64_t rows, rows_pad;
-    int64_t k, kb;
-    int64_t chunks;        // chunks per block
-    int s, b;
     int vec_ok;            // 16-byte aligned loads allowed
     uint8_t* slices;       // null: count only, nothing is stored
     int32_t* exps;
+};
+
+// A launch splits the vectors of up to two operands (same k, block length, format and slice count): the first wg_first
+// workgroups of the grid belong to v[0], the rest to v[1].
+struct SplitArgs {
+    SplitVectors v[2];
+    unsigned wg_first;     // a multiple of 8
+    int64_t k, kb;
+    int64_t chunks;        // chunks per block
+    int s, b;
     int* flags;            // [0]: non-finite input seen; [1]: slice count (count-only mode)
 };
 
@@ -104,14 +114,23 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
     // Workgroups are handed to the eight XCDs (each with an L2 of its own) round-robin by their index.  Neighbouring
     // vectors share the cache lines of the slice layout (a line holds the 16-byte pieces of eight vectors in the
     // FP6 planes, the 64-byte chunks of two vectors otherwise), so consecutive vectors go to workgroups of the SAME
-    // XCD, where the partial lines meet in one L2 before they are written back.  gridDim.x is a multiple of 8.
-    const int64_t wg = (int64_t)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    // XCD, where the partial lines meet in one L2 before they are written back.  Each operand's share of the grid is a multiple of 8.
+    const bool second = blockIdx.x >= a.wg_first;                    // which operand this workgroup works on
+    const double* const vX = second ? a.v[1].X : a.v[0].X;
+    const int64_t v_ldv = second ? a.v[1].ldv : a.v[0].ldv;
+    const int64_t v_rows = second ? a.v[1].rows : a.v[0].rows, v_rows_pad = second ? a.v[1].rows_pad : a.v[0].rows_pad;
+    const int v_vec_ok = second ? a.v[1].vec_ok : a.v[0].vec_ok;
+    uint8_t* const v_slices = second ? a.v[1].slices : a.v[0].slices;
+    int32_t* const v_exps = second ? a.v[1].exps : a.v[0].exps;
+    const unsigned li = blockIdx.x - (second ? a.wg_first : 0u);     // index and count inside the operand's part of the
+    const unsigned gl = second ? gridDim.x - a.wg_first : a.wg_first;   // grid; both multiples of 8, so li % 8 is the XCD
+    const int64_t wg = (int64_t)(li & 7) * (gl >> 3) + (li >> 3);
     const int64_t row = wg * RPB + threadIdx.x / TPR;
     const int64_t t = blockIdx.y;
     const int64_t k0 = t * a.kb;
     int64_t klen = a.k - k0;
     if (klen > a.kb) klen = a.kb;
-    if (row >= a.rows) klen = 0;                      // padding vectors are all zero
+    if (row >= v_rows) klen = 0;                      // padding vectors are all zero
     const int64_t padded = a.chunks * EPC;
     // Fixed-point scale of the working representation: an active element holds T = x^(p) / 2^(c_p - b) * 2^F as a
     // signed 64-bit integer.  |x^(p)| <= 2^(c_p) bounds |T| by 2^(b+F) = 2^60.
@@ -124,12 +143,12 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
     int pk[8 * U];
     bool nonfinite = false;
     int cmax = NO_ELEM;
-    const double* src = a.X + row * a.ldv + k0;
+    const double* src = vX + row * v_ldv + k0;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int64_t ke = 8 * ((int64_t)tr + (int64_t)TPR * u);
         uint64_t bits[8];
-        if (a.vec_ok && ke + 8 <= klen) {
+        if (v_vec_ok && ke + 8 <= klen) {
             const ulonglong2* v = reinterpret_cast<const ulonglong2*>(src + ke);
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
@@ -178,7 +197,7 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
                 cmax = o > cmax ? o : cmax;
             }
         }
-        if (a.slices == nullptr) {
+        if (v_slices == nullptr) {
             // count-only mode ("until x^(p) = 0", paragraph before Eq. 4): something is left before the (p+1)-th
             // slice, so this vector needs at least p + 1 of them
             if (cmax != NO_ELEM && tr == 0) atomicMax(a.flags + 1, p + 1);
@@ -192,7 +211,7 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
         c_prev = c;
 
         // ---- Eq. 5-8 element by element, eight codes per store
-        uint8_t* const dst_slice = a.slices + (size_t)((t * a.s + p) * a.chunks) * (size_t)a.rows_pad * ROWB;
+        uint8_t* const dst_slice = v_slices + (size_t)((t * a.s + p) * a.chunks) * (size_t)v_rows_pad * ROWB;
         uint64_t rmax = 0;                                             // largest |remainder| of this thread's active elements
         int cdorm = NO_ELEM;                                           // largest cd of its still dormant elements
         const int64_t round_bias = ((int64_t)1 << (F - 1)) - 1;
@@ -257,12 +276,12 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
                     w48 |= (uint64_t)(FMT == FMT_FP6_E3M2 ? encode_e3m2(qs[e], a.b) : encode_e2m3(qs[e], a.b)) << (6 * e);
-                if (ke < padded && a.slices != nullptr) {
+                if (ke < padded && v_slices != nullptr) {
                     const int64_t kc = ke / EPC;
                     const int o = (int)((ke % EPC) / 8), g = o >> 2, j = o & 3;
-                    uint8_t* const chunk = dst_slice + (size_t)kc * a.rows_pad * ROWB;
-                    uint8_t* const p16 = chunk + ((size_t)g * a.rows_pad + row) * 16;
-                    uint8_t* const p8 = chunk + (size_t)a.rows_pad * 32 + ((size_t)g * a.rows_pad + row) * 8;
+                    uint8_t* const chunk = dst_slice + (size_t)kc * v_rows_pad * ROWB;
+                    uint8_t* const p16 = chunk + ((size_t)g * v_rows_pad + row) * 16;
+                    uint8_t* const p8 = chunk + (size_t)v_rows_pad * 32 + ((size_t)g * v_rows_pad + row) * 8;
                     uint8_t* d32 = j == 0 ? p16 : j == 1 ? p16 + 8 : j == 2 ? p16 + 12 : p8 + 4;
                     uint8_t* d16 = j == 0 ? p16 + 4 : j == 1 ? p16 + 6 : j == 2 ? p8 : p8 + 2;
                     const bool low32 = (j & 1) == 0;                   // bytes 6j.. start 4-byte aligned for even j
@@ -273,9 +292,9 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
                 uint32_t c2[4];                                            // two codes each
 #pragma unroll
                 for (int e = 0; e < 4; ++e) c2[e] = encode_type2_pair<FP16>(qs[2 * e], qs[2 * e + 1], a.b);
-                if (ke < padded && a.slices != nullptr) {
+                if (ke < padded && v_slices != nullptr) {
                     const int64_t kc = ke / EPC;
-                    uint8_t* dst = dst_slice + ((size_t)kc * a.rows_pad + row) * CHUNK_BYTES + (ke % EPC) * (FP16 ? 2 : 1);
+                    uint8_t* dst = dst_slice + ((size_t)kc * v_rows_pad + row) * CHUNK_BYTES + (ke % EPC) * (FP16 ? 2 : 1);
                     if (FP16) {
                         uint4 w;
                         w.x = c2[0];
@@ -292,7 +311,7 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
                 }
             }
         }
-        if (tr == 0 && a.slices != nullptr) a.exps[(t * a.s + p) * a.rows_pad + row] = c;
+        if (tr == 0 && v_slices != nullptr) v_exps[(t * a.s + p) * v_rows_pad + row] = c;
         // this thread's candidate for the next exponent: remainders are rmax * 2^(unit - F)
         cmax = cdorm;
         if (rmax != 0) {
@@ -338,13 +357,22 @@ __global__ void __launch_bounds__(256) export_slices_kernel(const uint8_t* __res
 }
 
 // One workgroup per 256-vector tile and block: for every slice p, is c_p - c_(p+1) the same for all real vectors?
-__global__ void __launch_bounds__(256) delta_kernel(const int32_t* __restrict__ exps, int32_t* __restrict__ deltas, int64_t rows,
-                                                    int64_t rows_pad, int s) {
+// The first tiles_first workgroups of a grid row belong to the first operand, the rest to the second.
+struct DeltaOperand {
+    const int32_t* exps;
+    int32_t* deltas;
+    int64_t rows, rows_pad;
+};
+__global__ void __launch_bounds__(256) delta_kernel(DeltaOperand o0, DeltaOperand o1, unsigned tiles_first, int s) {
     __shared__ int ref;
-    const int64_t tile = blockIdx.x, t = blockIdx.y;
+    const bool second = blockIdx.x >= tiles_first;
+    const int32_t* const exps = second ? o1.exps : o0.exps;
+    int32_t* const deltas = second ? o1.deltas : o0.deltas;
+    const int64_t rows = second ? o1.rows : o0.rows, rows_pad = second ? o1.rows_pad : o0.rows_pad;
+    const int64_t tile = blockIdx.x - (second ? tiles_first : 0u), tiles = rows_pad / TILE, t = blockIdx.y;
     const int64_t row = tile * TILE + threadIdx.x;
     const int32_t* e = exps + (size_t)t * s * rows_pad;
-    int32_t* out = deltas + ((size_t)t * gridDim.x + tile) * s;
+    int32_t* out = deltas + ((size_t)t * tiles + tile) * s;
     for (int p = 0; p + 1 < s; ++p) {
         const int d = e[(size_t)p * rows_pad + row] - e[(size_t)(p + 1) * rows_pad + row];
         if (threadIdx.x == 0) ref = d;               // the first vector of a tile is always a real one
@@ -356,10 +384,12 @@ __global__ void __launch_bounds__(256) delta_kernel(const int32_t* __restrict__ 
 }
 
 template <int U, int TPR>
-hipError_t launch_split_cfg(const SplitArgs& a, int fmt, int64_t T, hipStream_t st) {
+hipError_t launch_split_cfg(const SplitArgs& a_in, int fmt, int64_t T, hipStream_t st) {
     constexpr int BLOCK = TPR < 256 ? 256 : TPR;
     constexpr int RPB = BLOCK / TPR;
-    dim3 grid((unsigned)((a.rows_pad + RPB - 1) / RPB), (unsigned)T);
+    SplitArgs a = a_in;
+    a.wg_first = (unsigned)(a.v[0].rows_pad / RPB);                     // rows_pad is a multiple of 256, RPB <= 4
+    dim3 grid(a.wg_first + (unsigned)(a.v[1].rows_pad / RPB), (unsigned)T);
     if (fmt == FMT_FP16) hipLaunchKernelGGL((split_kernel<U, TPR, FMT_FP16>), grid, dim3(BLOCK), 0, st, a);
     else if (fmt == FMT_FP6) hipLaunchKernelGGL((split_kernel<U, TPR, FMT_FP6>), grid, dim3(BLOCK), 0, st, a);
     else if (fmt == FMT_FP6_E3M2) hipLaunchKernelGGL((split_kernel<U, TPR, FMT_FP6_E3M2>), grid, dim3(BLOCK), 0, st, a);
@@ -376,11 +406,26 @@ hipError_t launch_transpose(const double* A, int64_t lda, int64_t m, int64_t k, 
     return hipGetLastError();
 }
 
-hipError_t launch_split(const double* X, int64_t ldv, const Plan& pl, const Operand& op, int* flags, hipStream_t st) {
+namespace {
+SplitVectors split_vectors(const double* X, int64_t ldv, const Plan& pl, const Operand* op) {
+    SplitVectors v;
+    memset(&v, 0, sizeof(v));
+    if (op == nullptr || op->rows == 0) return v;                                 // no vectors: no workgroups
+    v.X = X; v.ldv = ldv; v.rows = op->rows; v.rows_pad = op->rows_pad; v.slices = op->slices; v.exps = op->exps;
+    v.vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0) && (ldv % 2 == 0) && (pl.kb % 2 == 0 || pl.T == 1);
+    return v;
+}
+}  // namespace
+
+hipError_t launch_split(const double* X0, int64_t ldv0, const Operand* op0, const double* X1, int64_t ldv1, const Operand* op1,
+                        const Plan& pl, int* flags, hipStream_t st) {
     SplitArgs a;
-    a.X = X; a.ldv = ldv; a.rows = op.rows; a.rows_pad = op.rows_pad; a.k = pl.k; a.kb = pl.kb; a.chunks = pl.chunks;
-    a.s = pl.s; a.b = pl.b; a.slices = op.slices; a.exps = op.exps; a.flags = flags;
-    a.vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15) == 0) && (ldv % 2 == 0) && (pl.kb % 2 == 0 || pl.T == 1);
+    a.v[0] = split_vectors(X0, ldv0, pl, op0);
+    a.v[1] = split_vectors(X1, ldv1, pl, op1);
+    a.wg_first = 0;
+    a.k = pl.k; a.kb = pl.kb; a.chunks = pl.chunks; a.s = pl.s; a.b = pl.b; a.flags = flags;
+    if (a.v[0].rows_pad + a.v[1].rows_pad == 0 || pl.T == 0) return hipSuccess;
+    const int64_t vectors = (a.v[0].rows_pad + a.v[1].rows_pad) * pl.T;
     const int fmt = pl.fmt;
     const int64_t octets = pl.chunks * pl.epc / 8;                              // per vector and block, padded
     // sixteen elements per thread (U = 2) is the measured optimum: more elements per thread cost registers and with
@@ -388,7 +433,7 @@ hipError_t launch_split(const double* X, int64_t ldv, const Plan& pl, const Oper
     if (octets <= 64) return launch_split_cfg<1, 64>(a, fmt, pl.T, st);
     // a small problem (few vectors) is bound by the length of a thread's dependent chain, not by throughput: eight
     // elements per thread there (1024 x 1024: 0.080 -> 0.065 ms for both operands; no gain from 2048 vectors on)
-    if (op.rows_pad * pl.T <= 1024) {
+    if (vectors <= 2048) {
         if (octets <= 128) return launch_split_cfg<1, 128>(a, fmt, pl.T, st);
         if (octets <= 256) return launch_split_cfg<1, 256>(a, fmt, pl.T, st);
     }
@@ -408,13 +453,18 @@ hipError_t launch_count_slices(const double* X, int64_t ldv, const Plan& pl, int
     op.rows = rows;
     op.rows_pad = (rows + TILE - 1) / TILE * TILE;
     op.slices = nullptr; op.exps = nullptr; op.deltas = nullptr;
-    return launch_split(X, ldv, cp, op, flags, st);
+    return launch_split(X, ldv, &op, nullptr, 0, nullptr, cp, flags, st);
 }
 
-hipError_t launch_deltas(const Plan& pl, const Operand& op, hipStream_t st) {
-    if (op.rows == 0 || pl.T == 0) return hipSuccess;
-    hipLaunchKernelGGL(delta_kernel, dim3((unsigned)(op.rows_pad / TILE), (unsigned)pl.T), dim3(256), 0, st, op.exps, op.deltas,
-                       op.rows, op.rows_pad, pl.s);
+hipError_t launch_deltas(const Plan& pl, const Operand* op0, const Operand* op1, hipStream_t st) {
+    DeltaOperand o[2];
+    memset(o, 0, sizeof(o));
+    const Operand* ops[2] = {op0, op1};
+    for (int i = 0; i < 2; ++i)
+        if (ops[i] != nullptr && ops[i]->rows > 0) o[i] = DeltaOperand{ops[i]->exps, ops[i]->deltas, ops[i]->rows, ops[i]->rows_pad};
+    const unsigned t0 = (unsigned)(o[0].rows_pad / TILE), t1 = (unsigned)(o[1].rows_pad / TILE);
+    if (t0 + t1 == 0 || pl.T == 0) return hipSuccess;
+    hipLaunchKernelGGL(delta_kernel, dim3(t0 + t1, (unsigned)pl.T), dim3(256), 0, st, o[0], o[1], t0, pl.s);
     return hipGetLastError();
 }
 
