@@ -196,6 +196,32 @@ def test_dgemm_matches_oracle(fmt, m, n, k, k_block, s, phi, accum):
     ws.close()
 
 
+@pytest.mark.parametrize("fmt,k_block", [("fp8", 0), ("fp6", 0), ("fp16", 256)])
+def test_operands_off_the_16_byte_boundary_with_odd_leading_dimensions(fmt, k_block):
+    """A, B and C start one element (8 bytes) past a 16-byte boundary and have odd leading dimensions: the split
+    kernel's two-element loads are not allowed there, the result must not change."""
+    m, n, k, s = 270, 140, 600, 9
+    A, B = inputs.phi_pair(m, n, k, 1.0, seed=99)
+    lda, ldb, ldc = m + 1, k + 1, m + 1
+    bufA = torch.zeros(1 + k * lda, dtype=torch.float64, device="cuda")
+    bufB = torch.zeros(1 + n * ldb, dtype=torch.float64, device="cuda")
+    bufC = torch.full((1 + n * ldc,), float("nan"), dtype=torch.float64, device="cuda")
+    bufA[1:].view(k, lda)[:, :m] = torch.from_numpy(np.ascontiguousarray(A.T)).cuda()     # column-major m x k
+    bufB[1:].view(n, ldb)[:, :k] = torch.from_numpy(np.ascontiguousarray(B.T)).cuda()     # column-major k x n
+    Ad, Bd, Cd = bufA[1:], bufB[1:], bufC[1:]
+    assert Ad.data_ptr() % 16 == 8 and Bd.data_ptr() % 16 == 8
+    ws = device.Workspace.for_problem(m, n, k, FMT[fmt], s, k_block)
+    for accum in ("hw", "emu"):
+        Cd.fill_(float("nan"))
+        lib.ozaki_dgemm(m, n, k, Ad, lda, Bd, ldb, Cd, ldc, FMT[fmt], s, k_block, ACC[accum])
+        assert lib.ozaki_last_device_status() == 0
+        Cfull = Cd.view(n, ldc).cpu().numpy()
+        assert np.all(np.isnan(Cfull[:, m:])) and np.isnan(float(bufC[0]))
+        Cref = oz.ozaki_dgemm(A, B, fmt, s, k_block)
+        assert np.array_equal(np.ascontiguousarray(Cfull[:, :m].T).view(np.uint64), Cref.view(np.uint64))
+    ws.close()
+
+
 def test_slice_count_until_exhaustion_and_error_free_product():
     """The paper's own stopping rule (slice until the remainder is zero) and its consequence: with that many
     slices and all pairs, the pair products sum to the exact product (Eq. 9-10)."""
