@@ -34,7 +34,7 @@ DEFAULT_CONFIG = "c3_8192_fp8_emu"                      # the configuration the 
 # L2-fill + write-back bytes of one pair_gemm_kernel launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script (scaled by the 1 GiB copy-calibration kernel); see profiles/ozaki_dgemm_c3_8192_fp8_emu.md.  Only valid for
 # the configuration's calibrated slice count.
-MEASURED_TRAFFIC_BYTES = {("c3_8192_fp8_emu", "fp8"): 122.65 * 2 ** 30, ("c3_8192_fp8_emu", "fp6"): 91.25 * 2 ** 30}
+MEASURED_TRAFFIC_BYTES = {("c3_8192_fp8_emu", "fp8"): 120.91 * 2 ** 30, ("c3_8192_fp8_emu", "fp6"): 90.21 * 2 ** 30}
 
 
 def parse_args():
