@@ -57,7 +57,8 @@ enum {
                                    /* block length exceeds OZAKI_MAX_K_BLOCK                               */
     OZAKI_STATUS_WORKSPACE = 3,    /* no workspace set, or it is smaller than ozaki_workspace_min_bytes    */
     OZAKI_STATUS_HIP_ERROR = 4,    /* a HIP runtime call failed; see ozaki_last_hip_error                  */
-    OZAKI_STATUS_NONFINITE = 5     /* reported by ozaki_last_device_status: A or B held an Inf or NaN      */
+    OZAKI_STATUS_NONFINITE = 5,    /* reported by ozaki_last_device_status: A or B held an Inf or NaN      */
+    OZAKI_STATUS_STATIC_LIMIT = 6  /* ozaki_dgemm_static: the problem needs more than OZAKI_STATIC_SCRATCH_BYTES */
 };
 
 /* OR-ed into a num_slices argument: multiply all s*s slice pairs (the setting of the paper's Table 2 and
@@ -106,6 +107,27 @@ int ozaki_dgemm(int64_t m, int64_t n, int64_t k,
                 const double* A, int64_t lda, const double* B, int64_t ldb,
                 double* C, int64_t ldc,
                 int slice_format, int num_slices, int64_t k_block, int accum_mode);
+
+/*
+ * ozaki_dgemm_static -- ozaki_dgemm for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * the same bits in C as ozaki_dgemm, but the slices, exponents and slice-pair products live in a fixed array of
+ * OZAKI_STATIC_SCRATCH_BYTES bytes that is part of the library's device code (every GPU the library runs on holds
+ * one copy from the first call until the process ends); the workspace of ozaki_set_workspace is neither needed nor
+ * touched, and the call allocates and frees nothing.
+ *   Limit: ozaki_workspace_min_bytes(m, n, k, slice_format, num_slices, k_block) must not exceed
+ *   OZAKI_STATIC_SCRATCH_BYTES, else OZAKI_STATUS_STATIC_LIMIT is returned and nothing is launched (for example
+ *   m = n = k = 256 with 12 FP8 slices needs 5.6 MiB, m = n = 512, k = 2048 with 13 slices 49.1 MiB).
+ *   Every call on a GPU uses that GPU's one array, which keeps what the previous call left: the kernels overwrite
+ *   all they read, so nothing needs clearing between calls, but two calls that overlap in time on one GPU (two
+ *   streams, two host threads) race on it and give undefined results.  Enqueued on the stream of ozaki_set_stream.
+ *   An Inf/NaN input is reported by ozaki_last_device_status as for ozaki_dgemm.
+ */
+#define OZAKI_STATIC_SCRATCH_BYTES (64u << 20)
+int ozaki_dgemm_static(int64_t m, int64_t n, int64_t k,
+                       const double* A, int64_t lda, const double* B, int64_t ldb,
+                       double* C, int64_t ldc,
+                       int slice_format, int num_slices, int64_t k_block, int accum_mode);
 
 /*
  * ozaki_dgemm_scaled -- C := alpha (A B) + beta C, the GEMM of the BLAS that the paper emulates (Section 1), with

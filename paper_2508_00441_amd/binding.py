@@ -20,7 +20,8 @@ SLICE_FP6_E2M3 = 2
 SLICE_FP6_E3M2 = 3
 ACCUM_FP64_HW = 0
 ACCUM_FP64_INT_EMU = 1
-STATUS_OK, STATUS_INFEASIBLE, STATUS_WORKSPACE, STATUS_HIP_ERROR, STATUS_NONFINITE = 0, 1, 3, 4, 5
+STATUS_OK, STATUS_INFEASIBLE, STATUS_WORKSPACE, STATUS_HIP_ERROR, STATUS_NONFINITE, STATUS_STATIC_LIMIT = 0, 1, 3, 4, 5, 6
+STATIC_SCRATCH_BYTES = 64 << 20
 PAIRS_ALL = 0x100
 MAX_SLICES = 32
 MAX_K_BLOCK = 32768
@@ -33,6 +34,7 @@ _i64, _int, _vp, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_s
 SIGNATURES = {
     "ozaki_plan": (_int, [_i64, _int, ctypes.POINTER(_int), ctypes.POINTER(_int)]),
     "ozaki_dgemm": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int, _int, _i64, _int]),
+    "ozaki_dgemm_static": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int, _int, _i64, _int]),
     "ozaki_dgemm_scaled": (_int, [_i64, _i64, _i64, ctypes.c_double, _vp, _i64, _vp, _i64, ctypes.c_double, _vp, _i64, _int, _int,
                                   _i64, _int]),
     "ozaki_workspace_bytes_scaled": (_sz, [_i64, _i64, _i64, _int, _int, _i64]),
@@ -151,6 +153,11 @@ def ozaki_profile_read():
 def ozaki_dgemm(m, n, k, A, lda, B, ldb, C, ldc, slice_format, num_slices, k_block, accum_mode, check: bool = True) -> int:
     st = load().ozaki_dgemm(m, n, k, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, slice_format, num_slices, k_block, accum_mode)
     return _check(st, "ozaki_dgemm") if check else st
+
+
+def ozaki_dgemm_static(m, n, k, A, lda, B, ldb, C, ldc, slice_format, num_slices, k_block, accum_mode, check: bool = True) -> int:
+    st = load().ozaki_dgemm_static(m, n, k, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, slice_format, num_slices, k_block, accum_mode)
+    return _check(st, "ozaki_dgemm_static") if check else st
 
 
 def ozaki_dgemm_scaled(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, slice_format, num_slices, k_block, accum_mode,

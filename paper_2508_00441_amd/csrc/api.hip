@@ -26,6 +26,13 @@ struct State {
 };
 State g;
 
+// Work memory of ozaki_dgemm_static: one array per GPU the library runs on, part of the loaded code object (zero when
+// the object is loaded), so that the entry point never allocates.  Host code must not use the array's name as an
+// address: the per-device address comes from hipGetSymbolAddress, once per device, and is kept in static_scratch_ptr.
+static __device__ __align__(256) unsigned char static_scratch[OZAKI_STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+uint8_t* static_scratch_ptr[MAX_DEVICES] = {};
+
 constexpr size_t ALIGN = 256;
 constexpr size_t FLAG_BYTES = 256;
 constexpr size_t P_BUDGET = (size_t)160 << 30;        // resident pair products: well inside the 288 GB of one GPU
@@ -125,37 +132,45 @@ size_t minimum_bytes(const Plan& pl) {
 size_t product_bytes(const Plan& pl) { return align_up((size_t)pl.m * pl.n * sizeof(double)); }
 
 // Places every buffer in the workspace; returns false if it does not fit.
-bool carve(const Plan& pl, Carve& c, bool want_product = false) {
-    if (!g.ws) return false;
+struct WorkMem {
+    uint8_t* ptr;
+    size_t bytes;
+};
+WorkMem set_workspace() { return WorkMem{g.ws, g.ws_bytes}; }
+
+bool carve(const Plan& pl, Carve& c, bool want_product = false, WorkMem wm = set_workspace()) {
+    uint8_t* const ws = wm.ptr;
+    const size_t ws_bytes = wm.bytes;
+    if (!ws) return false;
     size_t off = 0;
-    c.flags = reinterpret_cast<int*>(g.ws);
+    c.flags = reinterpret_cast<int*>(ws);
     off += FLAG_BYTES;
-    c.At = reinterpret_cast<double*>(g.ws + off);
+    c.At = reinterpret_cast<double*>(ws + off);
     off += align_up((size_t)pl.m * pl.k * sizeof(double));
     c.A.rows = pl.m; c.A.rows_pad = pl.m_pad;
     c.B.rows = pl.n; c.B.rows_pad = pl.n_pad;
-    c.A.slices = g.ws + off; off += slices_bytes(pl, pl.m_pad);
-    c.B.slices = g.ws + off; off += slices_bytes(pl, pl.n_pad);
-    c.A.exps = reinterpret_cast<int32_t*>(g.ws + off); off += exps_bytes(pl, pl.m_pad);
-    c.B.exps = reinterpret_cast<int32_t*>(g.ws + off); off += exps_bytes(pl, pl.n_pad);
-    c.A.deltas = reinterpret_cast<int32_t*>(g.ws + off); off += deltas_bytes(pl, pl.m_pad);
-    c.B.deltas = reinterpret_cast<int32_t*>(g.ws + off); off += deltas_bytes(pl, pl.n_pad);
+    c.A.slices = ws + off; off += slices_bytes(pl, pl.m_pad);
+    c.B.slices = ws + off; off += slices_bytes(pl, pl.n_pad);
+    c.A.exps = reinterpret_cast<int32_t*>(ws + off); off += exps_bytes(pl, pl.m_pad);
+    c.B.exps = reinterpret_cast<int32_t*>(ws + off); off += exps_bytes(pl, pl.n_pad);
+    c.A.deltas = reinterpret_cast<int32_t*>(ws + off); off += deltas_bytes(pl, pl.m_pad);
+    c.B.deltas = reinterpret_cast<int32_t*>(ws + off); off += deltas_bytes(pl, pl.n_pad);
     c.W = nullptr;
-    if (want_product) { c.W = reinterpret_cast<double*>(g.ws + off); off += product_bytes(pl); }
-    if (off > g.ws_bytes) return false;
-    const size_t rest = g.ws_bytes - off, pb = pair_bytes(pl);
+    if (want_product) { c.W = reinterpret_cast<double*>(ws + off); off += product_bytes(pl); }
+    if (off > ws_bytes) return false;
+    const size_t rest = ws_bytes - off, pb = pair_bytes(pl);
     if (pb == 0) { c.S = nullptr; c.P = nullptr; c.chunk_pairs = pl.npairs; return true; }
     if (rest >= (size_t)pl.npairs * pb) {
         c.S = nullptr;
-        c.P = reinterpret_cast<float*>(g.ws + off);
+        c.P = reinterpret_cast<float*>(ws + off);
         c.chunk_pairs = pl.npairs;
         return true;
     }
     if (rest < sum_bytes(pl) + (size_t)pl.s * pb) return false;
-    c.S = reinterpret_cast<double*>(g.ws + off);
+    c.S = reinterpret_cast<double*>(ws + off);
     off += sum_bytes(pl);
-    c.P = reinterpret_cast<float*>(g.ws + off);
-    size_t fit = (g.ws_bytes - off) / pb;
+    c.P = reinterpret_cast<float*>(ws + off);
+    size_t fit = (ws_bytes - off) / pb;
     c.chunk_pairs = fit > (size_t)pl.npairs ? pl.npairs : (int)fit;
     return c.chunk_pairs >= pl.s;
 }
@@ -219,7 +234,8 @@ bool scalar_ok(double v) {
 // C = alpha * (A B) + beta * C.  (alpha, beta) = (1, 0): the product goes straight to C.  Otherwise it goes to the
 // workspace's product buffer and one more kernel combines it with C.  Error codes: argument positions of ozaki_dgemm.
 int dgemm_core(int64_t m, int64_t n, int64_t k, double alpha, const double* A, int64_t lda, const double* B, int64_t ldb,
-               double beta, double* C, int64_t ldc, int slice_format, int num_slices, int64_t k_block, int accum_mode) {
+               double beta, double* C, int64_t ldc, int slice_format, int num_slices, int64_t k_block, int accum_mode,
+               WorkMem wm = set_workspace()) {
     Plan pl;
     const int st = make_plan(m, n, k, slice_format, num_slices & ~OZAKI_PAIRS_ALL, k_block, (num_slices & OZAKI_PAIRS_ALL) != 0, pl);
     if (st != 0) return st;
@@ -236,7 +252,7 @@ int dgemm_core(int64_t m, int64_t n, int64_t k, double alpha, const double* A, i
     }
     Carve c;
     c.W = nullptr;
-    if ((k > 0 || scaled) && !carve(pl, c, scaled)) return OZAKI_STATUS_WORKSPACE;
+    if ((k > 0 || scaled) && !carve(pl, c, scaled, wm)) return OZAKI_STATUS_WORKSPACE;
     double* const out = scaled ? c.W : C;
     const int64_t ldo = scaled ? (m > 1 ? m : 1) : ldc;
     if (k == 0) {
@@ -317,15 +333,17 @@ int ozaki_set_workspace(void* dev_ptr, size_t bytes) {
 }
 
 int ozaki_last_device_status(void) {
-    if (!g.ws) {
-        HIP_TRY(hipStreamSynchronize(g.stream));
-        return 0;
-    }
-    int flags = 0;
-    HIP_TRY(hipMemcpyAsync(&flags, g.ws, sizeof(int), hipMemcpyDeviceToHost, g.stream));
+    // the flag words of the set workspace and of this device's static scratch (if ozaki_dgemm_static has used it)
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    uint8_t* places[2] = {g.ws, (dev >= 0 && dev < MAX_DEVICES) ? static_scratch_ptr[dev] : nullptr};
+    int flags[2] = {0, 0};
+    for (int i = 0; i < 2; ++i)
+        if (places[i]) HIP_TRY(hipMemcpyAsync(&flags[i], places[i], sizeof(int), hipMemcpyDeviceToHost, g.stream));
     HIP_TRY(hipStreamSynchronize(g.stream));
-    if (flags) HIP_TRY(hipMemsetAsync(g.ws, 0, FLAG_BYTES, g.stream));
-    return (flags & 1) ? OZAKI_STATUS_NONFINITE : 0;
+    for (int i = 0; i < 2; ++i)
+        if (flags[i]) HIP_TRY(hipMemsetAsync(places[i], 0, FLAG_BYTES, g.stream));
+    return ((flags[0] | flags[1]) & 1) ? OZAKI_STATUS_NONFINITE : 0;
 }
 
 int ozaki_last_hip_error(void) { return g.last_hip_error; }
@@ -337,6 +355,7 @@ const char* ozaki_status_string(int status) {
         case OZAKI_STATUS_WORKSPACE: return "workspace missing or too small";
         case OZAKI_STATUS_HIP_ERROR: return "HIP runtime error";
         case OZAKI_STATUS_NONFINITE: return "non-finite input";
+        case OZAKI_STATUS_STATIC_LIMIT: return "problem needs more work memory than the static scratch of ozaki_dgemm_static holds";
         default: return status < 0 ? "invalid argument (the negated value is its 1-based position)" : "unknown status";
     }
 }
@@ -365,6 +384,28 @@ int ozaki_profile_read(float* ms_out, int* launches_out) {
 int ozaki_dgemm(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb,
                 double* C, int64_t ldc, int slice_format, int num_slices, int64_t k_block, int accum_mode) {
     return dgemm_core(m, n, k, 1.0, A, lda, B, ldb, 0.0, C, ldc, slice_format, num_slices, k_block, accum_mode);
+}
+
+int ozaki_dgemm_static(int64_t m, int64_t n, int64_t k, const double* A, int64_t lda, const double* B, int64_t ldb,
+                       double* C, int64_t ldc, int slice_format, int num_slices, int64_t k_block, int accum_mode) {
+    Plan pl;
+    const int st = make_plan(m, n, k, slice_format, num_slices & ~OZAKI_PAIRS_ALL, k_block, (num_slices & OZAKI_PAIRS_ALL) != 0, pl);
+    if (st != 0) return st;
+    if (m > 0 && n > 0 && k > 0 && minimum_bytes(pl) > (size_t)OZAKI_STATIC_SCRATCH_BYTES) return OZAKI_STATUS_STATIC_LIMIT;
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail_hip(hipErrorInvalidDevice);
+    if (!static_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(static_scratch)));
+        if (!p) return fail_hip(hipErrorInvalidSymbol);
+        static_scratch_ptr[dev] = static_cast<uint8_t*>(p);
+    }
+    // Nothing in the scratch has to start at zero except the flag word, which is zero when the code object is loaded
+    // and is cleared by ozaki_last_device_status after it has reported a flag: every other buffer of the carve-up is
+    // written in full by the slicing and GEMM kernels before it is read.
+    return dgemm_core(m, n, k, 1.0, A, lda, B, ldb, 0.0, C, ldc, slice_format, num_slices, k_block, accum_mode,
+                      WorkMem{static_scratch_ptr[dev], (size_t)OZAKI_STATIC_SCRATCH_BYTES});
 }
 
 int ozaki_dgemm_scaled(int64_t m, int64_t n, int64_t k, double alpha, const double* A, int64_t lda, const double* B, int64_t ldb,
