@@ -68,7 +68,7 @@ def cpu_baseline_leg(cfg, s, A, B, Cd, sample):
     cols = np.sort(rng.choice(n, min(sample, n), replace=False))
     As, Bs = np.ascontiguousarray(A[rows, :]), np.ascontiguousarray(B[:, cols])
     t0 = time.perf_counter()
-    Cref = oz.ozaki_dgemm(As, Bs, cfg["fmt"], s, cfg["k_block"], mode="full" if cfg.get("pairs") == "all" else "triangle")
+    Cref = oz.ozaki_dgemm(As, Bs, cfg["fmt"], s, cfg["k_block"], mode="full" if cfg.get("pairs") == "all" else "triangle", accumulate="runs")
     t_cpu = time.perf_counter() - t0
     Csub = Cd[torch.from_numpy(cols).cuda()][:, torch.from_numpy(rows).cuda()].cpu().numpy().T
     bit_equal = bool(np.array_equal(Csub.view(np.uint64), Cref.view(np.uint64)))

@@ -15,8 +15,14 @@ Conventions (where the paper leaves a point open, the reading taken is stated he
   * Eq. 4's ceil(log2(max)) is evaluated exactly: the smallest integer c with max <= 2^c; c = 0 for a zero vector.
   * With num_slices = s on both operands the pairs used are those with p + q <= s + 1 ("triangle"),
     or all s*s ("full").  Accumulation order: anti-diagonals g = p+q from the largest g (smallest
-    magnitude) down to 2, p ascending inside an anti-diagonal.  Products of one anti-diagonal that carry
-    the same scale factor for an element are summed exactly first (see `block_result`).
+    magnitude) down to 2, p ascending inside an anti-diagonal.
+  * Accumulation (the paper says only that it is done in Type1 arithmetic and that its order was tuned):
+    the DEFINITION here is `accumulate="plain"`: the terms 2^(c_x+c_y) * product of Eq. 10 are added one
+    by one, each addition rounded to FP64, in the order above.  Two named variants exist beside it, both
+    readings of the same passage that a device may implement instead, each with the same order:
+    "runs" adds consecutive terms of one anti-diagonal that share their power-of-two scale exactly before
+    the one rounded addition; "exact" sums all terms of a block in a wide fixed-point integer and rounds
+    once (see `block_result`).
 """
 from __future__ import annotations
 
@@ -216,57 +222,97 @@ class BlockResult:
     S: np.ndarray                   # FP64 block sum
 
 
-def run_limit(plan: Plan) -> int:
-    """How many slice-pair products of one block may be summed in Type3 = FP32 without leaving the exact
-    window of Eq. 11: every product is at most k_block * 4^b units of 2^-2b, the window is 2^24 units."""
-    return max(1, (1 << M_FP32) // (plan.k_block << (2 * plan.b)))
+#: the accumulation rules of `block_result`
+ACCUMULATE_RULES = ("plain", "runs", "exact")
+
+#: "exact" rule: fraction bits of the fixed-point sum below the unit of the leading pair's product, 2^(c_x^(1)+c_y^(1)-2b)
+EXACT_WINDOW_BITS = 152
+
+
+def _accumulate_plain(terms, shape, add):
+    """Eq. 10 as written, in Type1 = FP64 arithmetic: S = fl(S + 2^(c_x+c_y) * product), term after term."""
+    S = np.zeros(shape, dtype=np.float64)
+    for P, e in terms:
+        S = add(S, np.ldexp(P.astype(np.float64), e))        # the term itself is exact: |P| <= 2^24, a power-of-two scale
+    return S
+
+
+def _accumulate_runs(terms, diagonals, shape, add):
+    """Variant: consecutive terms of one anti-diagonal whose scale 2^(c_x+c_y) is the same for an element are
+    summed exactly (integers in units of that scale), and each such run is added with one rounded FP64 addition.
+    An exact sum does not depend on how it is formed, so a device is free to form it in the matrix unit's FP32
+    accumulators (inside the window of Eq. 11) or in integer registers."""
+    S = np.zeros(shape, dtype=np.float64)
+    run_sum = np.zeros(shape, dtype=np.int64)          # exact sum of the current run, in units of 2^(run_e)
+    run_e = np.zeros(shape, dtype=np.int64)
+    open_run = np.zeros(shape, dtype=bool)
+    run_diag = None                                    # anti-diagonal of the previous pair
+
+    def flush(S, mask):
+        term = np.where(mask, np.ldexp(run_sum.astype(np.float64), run_e), 0.0)   # exact: |run_sum| < 2^53
+        return add(S, term)                                                        # adding +0.0 changes nothing
+
+    for (P, e), g in zip(terms, diagonals):
+        cont = open_run & (run_diag == g) & (e == run_e)   # a new anti-diagonal ends every run
+        run_diag = g
+        S = flush(S, open_run & ~cont)
+        run_sum = np.where(cont, run_sum + P, P)
+        run_e = e
+        open_run = np.ones(shape, dtype=bool)
+    return flush(S, open_run)
+
+
+_to_float_rne = np.frompyfunc(float, 1, 1)             # Python's int -> float conversion rounds to nearest, ties to even
+
+
+def _accumulate_exact(terms, e_lead, shape):
+    """Variant: the sum of Eq. 10 "performed without rounding errors" (remark after Eq. 11) as far as a fixed-point
+    integer reaches, rounded to FP64 once.  Per element the unit is 2^(e_lead - EXACT_WINDOW_BITS), e_lead being the
+    scale exponent of the leading pair (1,1); a term whose scale lies more than EXACT_WINDOW_BITS below e_lead is
+    cut to that unit towards minus infinity (it is below 2^-128 of the leading product's unit), every other term
+    is added exactly.  The order of the terms is irrelevant."""
+    acc = np.zeros(shape, dtype=object)                # Python integers: no overflow, no rounding
+    W = EXACT_WINDOW_BITS
+    for P, e in terms:
+        nz = P != 0
+        sh = np.where(nz, W + (e - e_lead), 0)         # zero products (exhausted slices carry c = 0) add nothing
+        Po = P.astype(object)
+        up = np.left_shift(Po, np.maximum(sh, 0).astype(object))
+        acc = acc + np.where(sh >= 0, up, np.right_shift(Po, np.maximum(-sh, 0).astype(object)))
+    S = _to_float_rne(acc).astype(np.float64)
+    return np.ldexp(S, e_lead - W)
 
 
 def block_result(Ab: np.ndarray, Bb: np.ndarray, plan: Plan, num_slices: int, mode: str = "triangle",
-                 add: Callable = hw_add, keep: bool = True, group: bool = True) -> BlockResult:
-    """One k-block: slice rows of Ab (m x kb) and columns of Bb (kb x n), form the pair products, accumulate.
-
-    Accumulation (element by element): the pairs are visited in `pair_order`.  With `group` set, consecutive
-    pairs of one anti-diagonal whose scale factor 2^(c_x+c_y) is the same for that element are first summed
-    exactly (integers in units of 2^-2b; a device may form such sums in the matrix unit as far as the FP32
-    window of Eq. 11 allows, see `run_limit`, and in integer registers beyond it -- exact sums do not depend
-    on how they are formed) and each such run is then added with one rounded FP64 addition.
-    Without `group` every product is added on its own.
-    """
+                 add: Callable = hw_add, keep: bool = True, accumulate: str = "plain") -> BlockResult:
+    """One k-block: slice rows of Ab (m x kb) and columns of Bb (kb x n), form the pair products, accumulate them
+    element by element in `pair_order` with the rule `accumulate` ("plain" is the definition; see the module
+    docstring and the three functions above)."""
+    if accumulate not in ACCUMULATE_RULES:
+        raise ValueError(accumulate)
     sa, ca, _ = slice_rows(Ab, plan.rho, num_slices)
     sb, cb, _ = slice_rows(np.ascontiguousarray(Bb.T), plan.rho, num_slices)
     qa = [slice_integers(s_, plan.b) for s_ in sa]
     qb = [slice_integers(s_, plan.b) for s_ in sb]
     limit = 1 << M_FP32
     shape = (Ab.shape[0], Bb.shape[1])
-    S = np.zeros(shape, dtype=np.float64)
     pairs = pair_order(num_slices, mode)
-    products = []
-    run_sum = np.zeros(shape, dtype=np.int64)          # exact sum of the current run, in units of 2^(run_e)
-    run_e = np.zeros(shape, dtype=np.int64)
-    open_run = np.zeros(shape, dtype=bool)
-    run_diag = None                                    # anti-diagonal of the previous pair
-
-    def flush(mask):
-        nonlocal S
-        term = np.where(mask, np.ldexp(run_sum.astype(np.float64), run_e), 0.0)   # exact: |run_sum| < 2^53
-        S = add(S, term)                                                           # adding +0.0 changes nothing
-
+    products, terms = [], []
     for (p, q) in pairs:
         P = pair_product_int(qa[p - 1], qb[q - 1])
         if P.size and np.max(np.abs(P)) > limit:
             raise AssertionError("pair product exceeds the exact FP32 range (Eq. 11 violated)")
         e = (ca[p - 1][:, None] + cb[q - 1][None, :] - 2 * plan.b).astype(np.int64)   # 2^(c_x+c_y) * 2^-2b
-        same_diag = group and run_diag == p + q        # a new anti-diagonal ends every run
-        run_diag = p + q
-        cont = open_run & same_diag & (e == run_e)
-        flush(open_run & ~cont)
-        run_sum = np.where(cont, run_sum + P, P)
-        run_e = e
-        open_run = np.ones(shape, dtype=bool)
+        terms.append((P, e))
         if keep:
             products.append(P)
-    flush(open_run)
+    if accumulate == "plain":
+        S = _accumulate_plain(terms, shape, add)
+    elif accumulate == "runs":
+        S = _accumulate_runs(terms, [p + q for p, q in pairs], shape, add)
+    else:
+        e_lead = (ca[0][:, None] + cb[0][None, :] - 2 * plan.b).astype(np.int64)
+        S = _accumulate_exact(terms, e_lead, shape)
     return BlockResult(sa, sb, ca, cb, pairs, products, S)
 
 
@@ -276,10 +322,10 @@ def hw_mul(x, y):
 
 
 def ozaki_dgemm(A: np.ndarray, B: np.ndarray, fmt: str = "fp8", num_slices: int = 11, k_block: int = 0,
-                mode: str = "triangle", add: Callable = hw_add, return_blocks: bool = False, group: bool = True,
+                mode: str = "triangle", add: Callable = hw_add, return_blocks: bool = False, accumulate: str = "plain",
                 alpha: float = 1.0, beta: float = 0.0, C0: np.ndarray = None, mul: Callable = hw_mul):
     """C = A B by the Ozaki scheme with inner-product-wise blocking (Section 4.3): every block's sum is
-    formed first, then added to C in FP64, blocks in ascending k.
+    formed first (rule `accumulate`, see `block_result`), then added to C in FP64, blocks in ascending k.
 
     With alpha / beta (the GEMM of the BLAS the paper emulates, Section 1; the scaling needs the FP64
     multiplication that Section 4.2 emulates next to the addition) the product P formed as above is combined as
@@ -297,7 +343,7 @@ def ozaki_dgemm(A: np.ndarray, B: np.ndarray, fmt: str = "fp8", num_slices: int 
         plan = make_plan(k, fmt, k_block)
         for t in range(plan.num_blocks):
             k0, k1 = t * plan.k_block, min(k, (t + 1) * plan.k_block)
-            br = block_result(A[:, k0:k1], B[k0:k1, :], plan, num_slices, mode, add, keep=return_blocks, group=group)
+            br = block_result(A[:, k0:k1], B[k0:k1, :], plan, num_slices, mode, add, keep=return_blocks, accumulate=accumulate)
             C = add(C, br.S)
             if return_blocks:
                 blocks.append(br)

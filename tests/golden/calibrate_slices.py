@@ -49,7 +49,7 @@ def calibrate(name, cfg):
     rows = []
     s_bound = s_native = None
     for s in range(4, 33):
-        C = oz.ozaki_dgemm(As, Bs, cfg["fmt"], s, cfg["k_block"])
+        C = oz.ozaki_dgemm(As, Bs, cfg["fmt"], s, cfg["k_block"], accumulate="runs")
         e_ab, e_c, _, _ = exact.sampled_errors(As, Bs, ent, [C[i, j] for i, j in ent])
         rows.append((s, e_ab, e_c))
         if s_bound is None and e_ab <= bound:

@@ -142,7 +142,7 @@ def test_pair_products_are_bit_exact(fmt, m, n, k, k_block, s, phi):
     lib.ozaki_pair_products(m, n, k, Ad, m, Bd, k, FMT[fmt], s, k_block, P)
     assert lib.ozaki_last_device_status() == 0
     Pn = P.cpu().numpy()
-    _, blocks = oz.ozaki_dgemm(A, B, fmt, s, k_block, return_blocks=True)
+    _, blocks = oz.ozaki_dgemm(A, B, fmt, s, k_block, return_blocks=True, accumulate="runs")
     for t, br in enumerate(blocks):
         assert br.pairs == oz.pair_order(s)
         for z, Pref in enumerate(br.products):
@@ -186,7 +186,7 @@ def test_dgemm_matches_oracle(fmt, m, n, k, k_block, s, phi, accum):
     Cfull = Cd.cpu().numpy()
     C = Cfull[:, :m].T
     assert np.all(np.isnan(Cfull[:, m:]))                         # the padding of ldc is not touched
-    Cref = oz.ozaki_dgemm(A, B, fmt, s, k_block)
+    Cref = oz.ozaki_dgemm(A, B, fmt, s, k_block, accumulate="runs")
     assert np.array_equal(C.view(np.uint64), Cref.view(np.uint64))
     # the stated bound against the exact product, on sampled entries, next to a native FP64 GEMM
     ent = exact.sample_entries(m, n, 12, seed=m)
@@ -217,7 +217,7 @@ def test_operands_off_the_16_byte_boundary_with_odd_leading_dimensions(fmt, k_bl
         assert lib.ozaki_last_device_status() == 0
         Cfull = Cd.view(n, ldc).cpu().numpy()
         assert np.all(np.isnan(Cfull[:, m:])) and np.isnan(float(bufC[0]))
-        Cref = oz.ozaki_dgemm(A, B, fmt, s, k_block)
+        Cref = oz.ozaki_dgemm(A, B, fmt, s, k_block, accumulate="runs")
         assert np.array_equal(np.ascontiguousarray(Cfull[:, :m].T).view(np.uint64), Cref.view(np.uint64))
     ws.close()
 
@@ -258,7 +258,7 @@ def test_slice_count_until_exhaustion_and_error_free_product():
     lib.ozaki_dgemm(40, 24, 96, Ad, 40, Bd, 96, Cd, 40, FMT["fp8"], s | lib.PAIRS_ALL, 0, ACC["emu"])
     C = Cd.cpu().numpy().T
     ws.close()
-    assert np.array_equal(C.view(np.uint64), oz.ozaki_dgemm(A, B, "fp8", s, 0, mode="full").view(np.uint64))
+    assert np.array_equal(C.view(np.uint64), oz.ozaki_dgemm(A, B, "fp8", s, 0, mode="full", accumulate="runs").view(np.uint64))
     for i in range(0, 40, 7):
         for j in range(0, 24, 5):
             ex = exact.exact_dot(A[i, :], B[:, j])
@@ -275,7 +275,7 @@ def test_scaled_dgemm_matches_oracle(fmt, m, n, k, k_block, s, accum):
     Ad, Bd = _upload(A, B)
     ldc = m + 5
     ws = device.Workspace.for_problem(m, n, k, FMT[fmt], s, k_block, scaled=True)
-    P = oz.ozaki_dgemm(A, B, fmt, s, k_block)
+    P = oz.ozaki_dgemm(A, B, fmt, s, k_block, accumulate="runs")
     for alpha, beta in ((-2.5, 0.0), (1.0, 1.0), (0.3, -1.7), (0.0, 2.0), (1.0, 0.0)):
         Cfull = np.full((n, ldc), np.nan)
         if beta != 0.0:
@@ -285,7 +285,7 @@ def test_scaled_dgemm_matches_oracle(fmt, m, n, k, k_block, s, accum):
         assert lib.ozaki_last_device_status() == 0
         out = Cd.cpu().numpy()
         assert np.all(np.isnan(out[:, m:]))
-        want = oz.ozaki_dgemm(A, B, fmt, s, k_block, alpha=alpha, beta=beta, C0=C0)
+        want = oz.ozaki_dgemm(A, B, fmt, s, k_block, alpha=alpha, beta=beta, C0=C0, accumulate="runs")
         assert np.array_equal(out[:, :m].T.view(np.uint64), want.view(np.uint64)), (alpha, beta)
         if (alpha, beta) == (1.0, 0.0):
             assert np.array_equal(want.view(np.uint64), P.view(np.uint64))
@@ -310,7 +310,7 @@ def test_all_pairs_mode_matches_oracle(fmt, m, n, k, k_block, s, phi, accum):
     lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, FMT[fmt], s | lib.PAIRS_ALL, k_block, ACC[accum])
     assert lib.ozaki_last_device_status() == 0
     C = device.from_device_colmajor(Cd)
-    Cref, blocks = oz.ozaki_dgemm(A, B, fmt, s, k_block, mode="full", return_blocks=True)
+    Cref, blocks = oz.ozaki_dgemm(A, B, fmt, s, k_block, mode="full", return_blocks=True, accumulate="runs")
     assert np.array_equal(C.view(np.uint64), Cref.view(np.uint64))
     if accum == "hw":
         T, npairs = len(blocks), s * s
@@ -521,7 +521,7 @@ def test_full_size_configs_on_sampled_rows_and_columns(name):
     cols = np.sort(rng.choice(n, ns, replace=False))
     rows[0], cols[-1] = 0, n - 1
     Csub = Cd[torch.from_numpy(cols).cuda()][:, torch.from_numpy(rows).cuda()].cpu().numpy().T
-    Cref = oz.ozaki_dgemm(A[rows, :], B[:, cols], fmt, s, kb)
+    Cref = oz.ozaki_dgemm(A[rows, :], B[:, cols], fmt, s, kb, accumulate="runs")
     assert np.array_equal(Csub.view(np.uint64), Cref.view(np.uint64))
     ent = [(int(i), int(j)) for i, j in zip(rng.integers(0, ns, 8), rng.integers(0, ns, 8))]
     got = [Csub[i, j] for i, j in ent]
@@ -541,7 +541,7 @@ def test_dgemm_can_be_captured_in_a_hip_graph_and_replayed():
     Ad, Bd = _upload(A, B)
     Cd = torch.zeros((n, m), dtype=torch.float64, device="cuda")
     ws = device.Workspace.for_problem(m, n, k, FMT["fp8"], s, 0)
-    want = [oz.ozaki_dgemm(A, B, "fp8", s, 0), oz.ozaki_dgemm(A2, B2, "fp8", s, 0)]
+    want = [oz.ozaki_dgemm(A, B, "fp8", s, 0, accumulate="runs"), oz.ozaki_dgemm(A2, B2, "fp8", s, 0, accumulate="runs")]
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     graph = torch.cuda.CUDAGraph()
@@ -596,5 +596,5 @@ def test_random_shapes_and_parameters_match_oracle(fmt, m, n, k, kb, s, full, ph
     assert lib.ozaki_last_device_status() == 0
     C = device.from_device_colmajor(Cd)
     ws.close()
-    Cref = oz.ozaki_dgemm(A, B, fmt, s, kb, mode="full" if full else "triangle")
+    Cref = oz.ozaki_dgemm(A, B, fmt, s, kb, mode="full" if full else "triangle", accumulate="runs")
     assert np.array_equal(C.view(np.uint64), Cref.view(np.uint64))

@@ -349,43 +349,89 @@ def test_scaling_and_permutation_invariants():
         assert np.array_equal(P4, P.T)
 
 
-def test_equal_scale_runs_are_summed_exactly_before_the_fp64_addition():
-    """Rows/columns inside one binade follow a regular exponent ladder, so every anti-diagonal carries one
-    scale factor; the grouped accumulation must then equal: exact sum of each run of equal-scale products
-    inside an anti-diagonal (rational arithmetic here), one FP64 addition per run."""
+def _read_hex_fixture(path):
+    out = {}
+    with open(path) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                name, *vals = line.split()
+                out[name] = np.array([float.fromhex(v) for v in vals])
+    return out
+
+
+def test_accumulation_rules_on_the_hand_derived_case(golden_dir):
+    """Section 3 (after Eq. 11), Section 4 (order of accumulation): a 2 x 2 x 3 product worked with pencil and paper
+    (tests/golden/accumulation_rules_2x2x3.txt) on which adding Eq. 10's terms one by one in FP64 (the definition,
+    "plain") and adding equal-scale terms of an anti-diagonal exactly first ("runs") give different bits, and a
+    1 x 1 x 3 product that sits on the cut of the fixed-point window of the "exact" rule."""
+    g = _read_hex_fixture(os.path.join(golden_dir, "accumulation_rules_2x2x3.txt"))
+    A, B = g["A"].reshape(2, 3), g["B"].reshape(3, 2)
+    for rule in oz.ACCUMULATE_RULES:
+        C = oz.ozaki_dgemm(A, B, "fp8", 3, 0, accumulate=rule)
+        assert np.array_equal(C.view(np.uint64), g["C_" + rule].reshape(2, 2).view(np.uint64)), rule
+        Csw = oz.ozaki_dgemm(A, B, "fp8", 3, 0, accumulate=rule, add=softfloat.soft_add)
+        assert np.array_equal(Csw.view(np.uint64), C.view(np.uint64)), rule
+    assert oz.ozaki_dgemm(A, B)[0, 0] != oz.ozaki_dgemm(A, B, accumulate="runs")[0, 0]      # the default is the plain rule
+    # the fixture's own claim about the exact value, in rationals
+    assert exact.exact_dot(A[0, :], B[:, 0]) == Fraction(1, 2 ** 14) + Fraction(1, 2 ** 62) == Fraction(float(g["C_runs"][0]))
+    a2, b2 = g["a2"].reshape(1, 3), g["b2"].reshape(3, 1)
+    for rule in oz.ACCUMULATE_RULES:
+        assert oz.ozaki_dgemm(a2, b2, "fp8", 3, 0, accumulate=rule)[0, 0] == g["c2_" + rule][0], rule
+    assert exact.round_fraction_to_double(exact.exact_dot(a2[0], b2[:, 0])) == g["c2_correctly_rounded"][0]
+
+
+def test_exact_rule_with_all_slices_and_all_pairs_is_the_correctly_rounded_product():
+    """Remark after Eq. 11: without rounding errors the sum of Eq. 10 IS the inner product.  With every slice, every
+    pair and all scales inside the fixed-point window, the "exact" rule must therefore return the exact product
+    (big-integer arithmetic of exact.py) rounded once; with k-blocking, the correctly rounded block products added
+    in FP64."""
+    rng = np.random.default_rng(77)
+    m, n, k = 6, 5, 48
+    A = inputs.phi_matrix(m, k, 1.5, rng)
+    B = inputs.phi_matrix(k, n, 1.5, rng)
+    A[2, :] = inputs.uniform_1_10(1, k, rng)[0]
+    for fmt, kb in (("fp8", 0), ("fp16", 0), ("fp6_e3m2", 0), ("fp8", 16)):
+        plan = oz.make_plan(k, fmt, kb)
+        s_full = 0
+        for t in range(plan.num_blocks):
+            k0, k1 = t * plan.k_block, min(k, (t + 1) * plan.k_block)
+            s_full = max(s_full, len(oz.slice_to_exhaustion(A[:, k0:k1], plan.rho)[0]),
+                         len(oz.slice_to_exhaustion(B[k0:k1, :].T.copy(), plan.rho)[0]))
+        C = oz.ozaki_dgemm(A, B, fmt, s_full, kb, mode="full", accumulate="exact")
+        for i in range(m):
+            for j in range(n):
+                want = 0.0
+                for t in range(plan.num_blocks):
+                    k0, k1 = t * plan.k_block, min(k, (t + 1) * plan.k_block)
+                    want = want + exact.round_fraction_to_double(exact.exact_dot(A[i, k0:k1], B[k0:k1, j]))
+                assert C[i, j] == want, (fmt, kb, i, j)
+
+
+def test_the_three_accumulation_rules_agree_within_rounding_and_runs_round_less_often():
+    """The rules differ only in where FP64 roundings happen: on a regular exponent ladder (rows inside one binade)
+    every anti-diagonal carries one scale, so "runs" performs one addition per anti-diagonal; all three stay within
+    the bound of a plain FP64 GEMM of the exact product."""
     rng = np.random.default_rng(31)
     m, n, k = 4, 3, 64
     A = inputs.full_mantissa_one_binade(m, k, rng) * np.where(rng.random((m, k)) < 0.5, -1.0, 1.0)
     B = (inputs.full_mantissa_one_binade(n, k, rng) * np.where(rng.random((n, k)) < 0.5, -1.0, 1.0)).T.copy()
+    ent = [(i, j) for i in range(m) for j in range(n)]
     for fmt, kb, s in (("fp8", 0, 7), ("fp16", 16, 4), ("fp8", 16, 6)):
-        plan = oz.make_plan(k, fmt, kb)
-        gmax = oz.run_limit(plan)
-        assert gmax == (1 << 24) // (plan.k_block * 4 ** plan.b)
-        C, blocks = oz.ozaki_dgemm(A, B, fmt, s, kb, return_blocks=True)
-        want = np.zeros((m, n))
-        for br in blocks:
-            S = np.zeros((m, n))
-            for i in range(m):
-                for j in range(n):
-                    run, run_scale, run_open, run_diag, acc, n_adds = Fraction(0), None, False, None, 0.0, 0
-                    for (p, q), P in zip(br.pairs, br.products):
-                        scale = int(br.c_a[p - 1][i] + br.c_b[q - 1][j])
-                        if run_open and (scale != run_scale or p + q != run_diag):
-                            acc = acc + float(run)          # float(Fraction) is exact here: a short integer times 2^e
-                            n_adds += 1
-                            run = Fraction(0)
-                        run += Fraction(int(P[i, j])) * Fraction(2) ** (scale - 2 * plan.b)
-                        run_scale, run_diag, run_open = scale, p + q, True
-                    S[i, j] = acc + float(run)
-                    assert n_adds + 1 == len({p + q for p, q in br.pairs})      # regular ladder: one addition per anti-diagonal
-            want = want + S
-        assert np.array_equal(C.view(np.uint64), want.view(np.uint64)), fmt
-        # the ladder is regular here: fewer FP64 additions than pairs, and never a worse result than pair-by-pair
-        ent = [(i, j) for i in range(m) for j in range(n)]
-        C_plain = oz.ozaki_dgemm(A, B, fmt, s, kb, group=False)
-        e_grouped = exact.sampled_errors(A, B, ent, [C[i, j] for i, j in ent])[0]
-        e_plain = exact.sampled_errors(A, B, ent, [C_plain[i, j] for i, j in ent])[0]
-        assert e_grouped <= e_plain * 1.5 + 2.0 ** -60
+        counts = {}
+        for rule in ("plain", "runs"):
+            calls = [0]
+
+            def counting_add(x, y, calls=calls):
+                calls[0] += int(np.count_nonzero(y[0, 0] if np.ndim(y) else y) > 0)
+                return x + y
+            oz.ozaki_dgemm(A[:1], B[:, :1], fmt, s, kb, accumulate=rule, add=counting_add)
+            counts[rule] = calls[0]
+        assert counts["runs"] < counts["plain"]
+        errs = {}
+        for rule in oz.ACCUMULATE_RULES:
+            C = oz.ozaki_dgemm(A, B, fmt, s, kb, accumulate=rule)
+            errs[rule] = exact.sampled_errors(A, B, ent, [C[i, j] for i, j in ent])[0]
+        assert errs["exact"] <= errs["runs"] * 1.5 + 2.0 ** -60 and errs["runs"] <= errs["plain"] * 1.5 + 2.0 ** -60
 
 
 def test_pair_order_is_least_significant_first():
