@@ -124,16 +124,16 @@ def main():
     s = args.num_slices or inputs.NUM_SLICES.get(args.config) or inputs.PAPER_NUM_SLICES[args.config]
     all_pairs = cfg.get("pairs") == "all"
     pairs = s * s if all_pairs else s * (s + 1) // 2
-    s_arg = s | lib.PAIRS_ALL if all_pairs else s
+    pair_set = lib.PAIRS_ALL if all_pairs else lib.PAIRS_TRIANGLE
     fmt_id, acc_id = lib.SLICE_FORMATS[fmt], lib.ACCUM_MODES[cfg["accum"]]
 
     A, B = inputs.config_pair(cfg, seed=0)
     Ad, Bd = device.to_device_colmajor(A), device.to_device_colmajor(B)
     Cd = torch.empty((n, m), dtype=torch.float64, device="cuda")
-    ws = device.Workspace.for_problem(m, n, k, fmt_id, s_arg, kb)
+    ws = device.Workspace.for_problem(m, n, k, fmt_id, s, kb, pair_set=pair_set)
 
     def step():
-        lib.ozaki_dgemm(m, n, k, Ad, m, Bd, k, Cd, m, fmt_id, s_arg, kb, acc_id)
+        lib.ozaki_dgemm_ex(m, n, k, Ad, m, Bd, k, Cd, m, fmt_id, s, kb, acc_id, pair_set, lib.SUM_RUNS, 0)
 
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")

@@ -20,11 +20,20 @@ from __future__ import annotations
 
 import numpy as np
 
-#: significand bits including the hidden bit (the paper's m_Type2, Section 3)
-SIGNIFICAND_BITS = {"fp8": 4, "fp16": 11, "fp6": 4, "fp6_e3m2": 3}
+#: significand bits including the hidden bit (the paper's m_Type2, Section 3).  "int8" is the comparison path on the
+#: integer matrix unit (the variant of the scheme Section 2 cites): a two's-complement byte holds the integers
+#: -128 .. 127, so the symmetric range |q| <= 2^b of Eq. 5-8 fits for b <= 6.
+SIGNIFICAND_BITS = {"fp8": 4, "fp16": 11, "fp6": 4, "fp6_e3m2": 3, "int8": 6}
+
+#: significand bits of the accumulator type (the paper's m_Type3): FP32, or INT32 for int8 slices.  An INT32 sum is
+#: exact up to 2^31 - 1 in magnitude, one short of the power of two Eq. 1 is written for, hence EXACT_WINDOW.
+ACCUMULATOR_BITS = {"fp8": 24, "fp16": 24, "fp6": 24, "fp6_e3m2": 24, "int8": 31}
+
+#: largest magnitude, in units of the product of two slice units, that the matrix unit accumulates exactly
+EXACT_WINDOW = {"fp8": 1 << 24, "fp16": 1 << 24, "fp6": 1 << 24, "fp6_e3m2": 1 << 24, "int8": (1 << 31) - 1}
 
 #: the stored code holds slice * 2^CODE_SHIFT (nonzero only for FP6 E2M3, see above)
-CODE_SHIFT = {"fp8": 0, "fp16": 0, "fp6": 1, "fp6_e3m2": 0}
+CODE_SHIFT = {"fp8": 0, "fp16": 0, "fp6": 1, "fp6_e3m2": 0, "int8": 0}
 
 
 def e4m3_decode_table() -> np.ndarray:
@@ -155,8 +164,22 @@ def e3m2_encode_exact(values: np.ndarray) -> np.ndarray:
     return out
 
 
-def encode_exact(fmt: str, values: np.ndarray) -> np.ndarray:
-    """Codes of the slice values `values` (= q * 2^-b, Eq. 8) in format `fmt`."""
+def int8_encode_exact(values: np.ndarray, b: int) -> np.ndarray:
+    """Two's-complement bytes of the integers q = values * 2^b; every q must be an integer in [-128, 127]."""
+    q = np.ldexp(np.asarray(values, dtype=np.float64), b)
+    if not np.array_equal(q, np.rint(q)) or (q.size and (q.min() < -128 or q.max() > 127)):
+        raise ValueError("slice entry is not an INT8 integer")
+    return q.astype(np.int8).view(np.uint8)
+
+
+def int8_decode(codes: np.ndarray, b: int) -> np.ndarray:
+    return np.ldexp(np.asarray(codes, dtype=np.uint8).view(np.int8).astype(np.float64), -b)
+
+
+def encode_exact(fmt: str, values: np.ndarray, b: int = None) -> np.ndarray:
+    """Codes of the slice values `values` (= q * 2^-b, Eq. 8) in format `fmt` (b is needed for "int8" only)."""
+    if fmt == "int8":
+        return int8_encode_exact(values, b)
     if fmt == "fp6":
         return e2m3_encode_exact(np.asarray(values, dtype=np.float64) * 2.0 ** CODE_SHIFT["fp6"])
     if fmt == "fp6_e3m2":
@@ -168,8 +191,10 @@ def encode_exact(fmt: str, values: np.ndarray) -> np.ndarray:
     raise ValueError(fmt)
 
 
-def decode(fmt: str, codes: np.ndarray) -> np.ndarray:
+def decode(fmt: str, codes: np.ndarray, b: int = None) -> np.ndarray:
     """Slice values (= q * 2^-b) of the codes."""
+    if fmt == "int8":
+        return int8_decode(codes, b)
     if fmt == "fp6":
         return e2m3_decode(codes) * 2.0 ** -CODE_SHIFT["fp6"]
     if fmt == "fp6_e3m2":

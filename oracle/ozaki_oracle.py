@@ -100,7 +100,12 @@ def make_plan(k: int, fmt: str, k_block: int = 0) -> Plan:
     k_block, not k).  A short last block uses the same rho (safe: its k is smaller)."""
     kb = k if k_block in (0, None) else min(k_block, k)
     m2 = formats.SIGNIFICAND_BITS[fmt]
-    rho = rho_const(kb, m2)
+    m3 = formats.ACCUMULATOR_BITS[fmt]
+    rho = rho_const(kb, m2, m3)
+    # Eq. 1 assumes that a sum of magnitude 2^m3 is still exact, which holds for a floating-point accumulator; an INT32
+    # accumulator ends at 2^31 - 1, so there one more bit goes to rho when k_block * 4^b would reach 2^31 exactly
+    while kb << (2 * (M_TYPE1 - rho)) > formats.EXACT_WINDOW[fmt] and rho <= M_TYPE1:
+        rho += 1
     if not slicing_feasible(rho):
         raise ValueError(f"slicing infeasible: rho={rho} for k_block={kb}, format {fmt}")
     nblk = -(-k // kb)
@@ -226,7 +231,7 @@ class BlockResult:
 ACCUMULATE_RULES = ("plain", "runs", "exact")
 
 #: "exact" rule: fraction bits of the fixed-point sum below the unit of the leading pair's product, 2^(c_x^(1)+c_y^(1)-2b)
-EXACT_WINDOW_BITS = 152
+EXACT_WINDOW_BITS = 144
 
 
 def _accumulate_plain(terms, shape, add):
@@ -294,14 +299,14 @@ def block_result(Ab: np.ndarray, Bb: np.ndarray, plan: Plan, num_slices: int, mo
     sb, cb, _ = slice_rows(np.ascontiguousarray(Bb.T), plan.rho, num_slices)
     qa = [slice_integers(s_, plan.b) for s_ in sa]
     qb = [slice_integers(s_, plan.b) for s_ in sb]
-    limit = 1 << M_FP32
+    limit = formats.EXACT_WINDOW[plan.fmt]
     shape = (Ab.shape[0], Bb.shape[1])
     pairs = pair_order(num_slices, mode)
     products, terms = [], []
     for (p, q) in pairs:
         P = pair_product_int(qa[p - 1], qb[q - 1])
         if P.size and np.max(np.abs(P)) > limit:
-            raise AssertionError("pair product exceeds the exact FP32 range (Eq. 11 violated)")
+            raise AssertionError("pair product exceeds the exact range of the accumulator (Eq. 11 violated)")
         e = (ca[p - 1][:, None] + cb[q - 1][None, :] - 2 * plan.b).astype(np.int64)   # 2^(c_x+c_y) * 2^-2b
         terms.append((P, e))
         if keep:
@@ -368,6 +373,6 @@ def split_operand(X_rows: np.ndarray, fmt: str, num_slices: int, k_block: int = 
     for t in range(plan.num_blocks):
         k0, k1 = t * plan.k_block, min(k, (t + 1) * plan.k_block)
         sl, cs, _ = slice_rows(X_rows[:, k0:k1], plan.rho, num_slices)
-        codes.append([formats.encode_exact(fmt, s_) for s_ in sl])
+        codes.append([formats.encode_exact(fmt, s_, plan.b) for s_ in sl])
         exps.append([c.astype(np.int32) for c in cs])
     return codes, exps, plan

@@ -18,22 +18,31 @@ SLICE_FP8_E4M3 = 0
 SLICE_FP16 = 1
 SLICE_FP6_E2M3 = 2
 SLICE_FP6_E3M2 = 3
+SLICE_INT8 = 4
 ACCUM_FP64_HW = 0
 ACCUM_FP64_INT_EMU = 1
-STATUS_OK, STATUS_INFEASIBLE, STATUS_WORKSPACE, STATUS_HIP_ERROR, STATUS_NONFINITE, STATUS_STATIC_LIMIT = 0, 1, 3, 4, 5, 6
+ACCUM_EXACT_FIXED = 2
+PAIRS_TRIANGLE, PAIRS_ALL = 0, 1
+SUM_RUNS, SUM_PLAIN = 0, 1
+STATUS_OK, STATUS_INFEASIBLE, STATUS_WORKSPACE, STATUS_HIP_ERROR, STATUS_NONFINITE, STATUS_STATIC_LIMIT, STATUS_SLICE_COUNT = 0, 1, 3, 4, 5, 6, 7
 STATIC_SCRATCH_BYTES = 64 << 20
-PAIRS_ALL = 0x100
 MAX_SLICES = 32
-MAX_K_BLOCK = 32768
 
-SLICE_FORMATS = {"fp8": SLICE_FP8_E4M3, "fp16": SLICE_FP16, "fp6": SLICE_FP6_E2M3, "fp6_e3m2": SLICE_FP6_E3M2}
-ACCUM_MODES = {"hw": ACCUM_FP64_HW, "emu": ACCUM_FP64_INT_EMU}
+SLICE_FORMATS = {"fp8": SLICE_FP8_E4M3, "fp16": SLICE_FP16, "fp6": SLICE_FP6_E2M3, "fp6_e3m2": SLICE_FP6_E3M2, "int8": SLICE_INT8}
+ACCUM_MODES = {"hw": ACCUM_FP64_HW, "emu": ACCUM_FP64_INT_EMU, "exact": ACCUM_EXACT_FIXED}
+PAIR_SETS = {"triangle": PAIRS_TRIANGLE, "full": PAIRS_ALL}
+SUM_RULES = {"runs": SUM_RUNS, "plain": SUM_PLAIN}
 
 #: every symbol include/ozaki_dgemm.h declares: name -> (restype, argtypes)
 _i64, _int, _vp, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
 SIGNATURES = {
     "ozaki_plan": (_int, [_i64, _int, ctypes.POINTER(_int), ctypes.POINTER(_int)]),
     "ozaki_dgemm": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int, _int, _i64, _int]),
+    "ozaki_dgemm_ex": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int, _int, _i64, _int, _int, _int, _sz]),
+    "ozaki_context_create": (_int, [ctypes.POINTER(_vp)]),
+    "ozaki_context_destroy": (_int, [_vp]),
+    "ozaki_context_use": (_int, [_vp]),
+    "ozaki_workspace_bytes_ex": (_sz, [_i64, _i64, _i64, _int, _int, _i64, _int, _int]),
     "ozaki_dgemm_static": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _int, _int, _i64, _int]),
     "ozaki_dgemm_scaled": (_int, [_i64, _i64, _i64, ctypes.c_double, _vp, _i64, _vp, _i64, ctypes.c_double, _vp, _i64, _int, _int,
                                   _i64, _int]),
@@ -50,7 +59,7 @@ SIGNATURES = {
     "ozaki_profile_enable": (_int, [_int]),
     "ozaki_profile_read": (_int, [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(_int)]),
     "ozaki_split": (_int, [_int, _i64, _i64, _vp, _i64, _int, _int, _i64, _vp, _vp]),
-    "ozaki_pair_products": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _int, _int, _i64, _vp]),
+    "ozaki_pair_products": (_int, [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _int, _int, _i64, _int, _int, _vp, _vp]),
     "ozaki_fp64_add_emulated": (_int, [_vp, _vp, _vp, _i64]),
 }
 
@@ -114,6 +123,26 @@ def ozaki_suggest_k_block(k, slice_format) -> int:
     return r
 
 
+def ozaki_context_create() -> int:
+    """A new context (its handle as an integer); select it with ozaki_context_use."""
+    h = _vp(None)
+    _check(load().ozaki_context_create(ctypes.byref(h)), "ozaki_context_create")
+    return int(h.value)
+
+
+def ozaki_context_destroy(handle: int) -> None:
+    _check(load().ozaki_context_destroy(handle), "ozaki_context_destroy")
+
+
+def ozaki_context_use(handle) -> None:
+    """Makes `handle` (None: the default context) the calling thread's current context."""
+    _check(load().ozaki_context_use(handle), "ozaki_context_use")
+
+
+def ozaki_workspace_bytes_ex(m, n, k, slice_format, num_slices, k_block, pair_set, minimum) -> int:
+    return int(load().ozaki_workspace_bytes_ex(m, n, k, slice_format, num_slices, k_block, pair_set, 1 if minimum else 0))
+
+
 def ozaki_workspace_bytes(m, n, k, slice_format, num_slices, k_block) -> int:
     return int(load().ozaki_workspace_bytes(m, n, k, slice_format, num_slices, k_block))
 
@@ -155,6 +184,13 @@ def ozaki_dgemm(m, n, k, A, lda, B, ldb, C, ldc, slice_format, num_slices, k_blo
     return _check(st, "ozaki_dgemm") if check else st
 
 
+def ozaki_dgemm_ex(m, n, k, A, lda, B, ldb, C, ldc, slice_format, num_slices, k_block, accum_mode, pair_set=PAIRS_TRIANGLE,
+                   sum_rule=SUM_RUNS, mem_cap=0, check: bool = True) -> int:
+    st = load().ozaki_dgemm_ex(m, n, k, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, slice_format, num_slices, k_block, accum_mode,
+                               pair_set, sum_rule, mem_cap)
+    return _check(st, "ozaki_dgemm_ex") if check else st
+
+
 def ozaki_dgemm_static(m, n, k, A, lda, B, ldb, C, ldc, slice_format, num_slices, k_block, accum_mode, check: bool = True) -> int:
     st = load().ozaki_dgemm_static(m, n, k, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, slice_format, num_slices, k_block, accum_mode)
     return _check(st, "ozaki_dgemm_static") if check else st
@@ -179,8 +215,10 @@ def ozaki_split(is_B, rows, k, X, ldx, slice_format, num_slices, k_block, slices
     return _check(st, "ozaki_split") if check else st
 
 
-def ozaki_pair_products(m, n, k, A, lda, B, ldb, slice_format, num_slices, k_block, P_out, check: bool = True) -> int:
-    st = load().ozaki_pair_products(m, n, k, _ptr(A), lda, _ptr(B), ldb, slice_format, num_slices, k_block, _ptr(P_out))
+def ozaki_pair_products(m, n, k, A, lda, B, ldb, slice_format, num_slices, k_block, P_out, pair_set=PAIRS_TRIANGLE, chained=0,
+                        run_len_out=None, check: bool = True) -> int:
+    st = load().ozaki_pair_products(m, n, k, _ptr(A), lda, _ptr(B), ldb, slice_format, num_slices, k_block, pair_set, chained,
+                                    _ptr(P_out), _ptr(run_len_out))
     return _check(st, "ozaki_pair_products") if check else st
 
 

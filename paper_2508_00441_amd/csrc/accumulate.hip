@@ -1,13 +1,14 @@
 // Accumulation of the slice-pair products into FP64 and the final rescale (paper Section 3, Eq. 10 and the
-// paragraph after Eq. 11; Section 4.2 for the integer-emulated variant; Section 4.3 for the block sum).
+// paragraph after Eq. 11; Section 4.2 for the integer-only variants; Section 4.3 for the block sum).
 //
 // For one k-block, element (i, j), the pairs (p, q) are visited least significant anti-diagonal first, p
 // ascending inside one.  The term of a pair is P_pq(i,j) * 2^e with e = (cA_p(i) - cA_1(i)) + (cB_q(j) - cB_1(j)).
-// Inside an anti-diagonal, consecutive pairs with the same e form a run.  A run is summed exactly (a 32-bit
-// integer in units of 2^-2b: at most 32 products of at most 2^24 units each) and added to the block sum S with
-// ONE rounded FP64 addition.  The GEMM kernel has already formed part of these sums in the matrix unit's
-// accumulators, as far as the exact FP32 window of Eq. 11 reaches (groups of at most run_limit pairs) and where a
-// whole tile shares the scale; the rest is merged here, element by element.  Then
+// Rule "runs": inside an anti-diagonal, consecutive pairs with the same e form a run.  A run is summed exactly (an
+// integer in units of 2^-2b: at most 32 products of at most 2^24, or 2^31 for INT8 slices, units each) and added to
+// the block sum S with ONE rounded FP64 addition.  The GEMM kernel has already formed part of these sums in the
+// matrix unit's accumulators, as far as the exact window of Eq. 11 reaches (groups of at most run_limit pairs) and
+// where a whole 32 x 32 tile shares the scale; the rest is merged here, element by element.  Rule "plain": every
+// product is added with its own rounded addition (the GEMM kernel then stores every pair on its own).  Then
 //     C   = S * 2^(cA_1(i) + cB_1(j))            first block
 //     C  += S * 2^(cA_1(i) + cB_1(j))            later blocks (one more FP64 addition)
 // Scaling by a power of two commutes with rounding (inside the normal range), so summing with exponents
@@ -15,10 +16,12 @@
 // 2^(cA_p + cB_q) as Eq. 10 writes it.  P_pq is the FP32 value left by the matrix unit; it already
 // contains the factor 2^-2b of the two slice entries and is an exact integer multiple of 2^-2b.  (FP6 codes
 // hold twice the slice value: the stored product is four times too large, an integer multiple of 2^-(2b-2); it
-// is read as that integer and still weighted 2^-2b.)
+// is read as that integer and still weighted 2^-2b.  INT8 slices leave the INT32 integer itself.)
 //
-// Two instantiations: hardware FP64 (int->double convert, ldexp, add -- no multiply) and integer-only
-// (fp64_emu.hpp), which executes no FP64 instruction at all and returns the same bits.
+// Three instantiations of the sum: hardware FP64 (int->double convert, ldexp, add -- no multiply); integer-emulated
+// FP64 (fp64_emu.hpp), which executes no FP64 instruction at all and returns the same bits; and the exact mode, a
+// 192-bit fixed-point integer per element that takes every run without rounding and is rounded once at the end
+// (integer-only as well).
 //
 // One workgroup handles one 32 x 32 MFMA tile position of a 256 x 256 tile (256 threads x 4 consecutive
 // columns of C each), reading the products in the order the GEMM kernel stored them.
@@ -34,8 +37,8 @@ namespace ozaki {
 namespace {
 
 struct AccArgs {
-    const float* P;          // [nz][tiles_n][tiles_m][TILE_ELEMS]
-    double* S;               // [tiles_n][tiles_m][TILE_ELEMS] running block sum (may be null when unused)
+    const float* P;          // [nz][tiles_n][tiles_m][TILE_ELEMS] FP32 (or INT32) words
+    uint64_t* S;             // running block sum, word w of an element at S[w * plane + element] (may be null when unused)
     double* C;
     int64_t ldc;
     const int32_t* ea;       // exponents of the block: [s][rows_pad_a]
@@ -44,17 +47,27 @@ struct AccArgs {
     int64_t m, n;
     int tiles_m, tiles_n;
     int two_b;               // 2b: a term is (stored product) * 2^(p_frac - two_b) * 2^e
-    int p_frac;              // the stored products are integer multiples of 2^-p_frac (2b; 2b - 2 for FP6 codes)
+    int p_frac;              // the stored products are integer multiples of 2^-p_frac (2b; 2b - 2 for FP6 codes; 0 for INT32)
     int read_S, write_S, add_to_C;
-    int allow_chain;
-    const int32_t* da;       // deltas of the block: [tiles_m][s]
-    const int32_t* db;       // [tiles_n][s]
+    int allow_chain;         // the GEMM kernel summed tile-wide runs
+    int merge;               // rule "runs": merge equal-scale products of an anti-diagonal element by element
+    const int32_t* da;       // deltas of the block: [rows_pad_a / 32][s]
+    const int32_t* db;       // [rows_pad_b / 32][s]
     PairOrder order;
     Pass pass;
 };
 
-template <bool EMU>
+// Is pair `pos` of anti-diagonal g (0-based position) stored on its own, i.e. does it start a run of the GEMM kernel?
+// dA / dB: the delta rows of the 32 rows / 32 columns concerned; p, q 0-based slice indices of the pair.
+__device__ __forceinline__ bool starts_run(const PairOrder& o, int allow_chain, const int32_t* dA, const int32_t* dB, int pos, int p,
+                                           int q) {
+    return pos % o.run_limit == 0 || !(allow_chain && pair_linked(dA, dB, p - 1, q + 1));
+}
+
+template <int MODE, bool PINT>
 __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
+    constexpr bool HW = MODE == ACC_HW, EMU = MODE == ACC_EMU, EXACT = MODE == ACC_EXACT;
+    typedef typename std::conditional<PINT, int64_t, int>::type run_t;      // exact sum of a run
     __shared__ int relA[MAX_SLICES][32];
     __shared__ int relB[MAX_SLICES][32];
     __shared__ uint32_t entries[MAX_PAIRS];           // stored runs of this tile: slot | p << 12 | q << 18 | first-of-diagonal << 24
@@ -85,22 +98,34 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
     const size_t tile_off = (size_t)tile * TILE_ELEMS + (size_t)pos * 1024 + (size_t)tid * 4;
     const size_t pair_stride = (size_t)a.tiles_m * a.tiles_n * TILE_ELEMS;
 
-    typedef typename std::conditional<EMU, uint64_t, double>::type acc_t;
-    acc_t S[4];
-    if (a.read_S) {
+    // the block sum of this thread's four elements, in the representation of the mode
+    double Sd[4];                                     // HW
+    RoundedSum E[4];                                  // EMU: integer while no rounding can occur, FP64 bits afterwards
+    Fixed192 X[4];                                    // EXACT
 #pragma unroll
-        for (int r = 0; r < 4; ++r) S[r] = reinterpret_cast<const acc_t*>(a.S)[tile_off + r];
-    } else {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) S[r] = 0;
+    for (int r = 0; r < 4; ++r) {
+        if constexpr (HW) Sd[r] = a.read_S ? __longlong_as_double((long long)a.S[tile_off + r]) : 0.0;
+        if constexpr (EMU) {
+            if (a.read_S) E[r].start_at(a.S[tile_off + r]);
+            else E[r].start_at_zero();
+        }
+        if constexpr (EXACT) {
+            if (a.read_S) {
+                X[r].w0 = a.S[tile_off + r];
+                X[r].w1 = a.S[pair_stride + tile_off + r];
+                X[r].w2 = a.S[2 * pair_stride + tile_off + r];
+            } else {
+                X[r].clear();
+            }
+        }
     }
 
-    // The stored runs of this tile, in accumulation order: a pair starts a run unless it is linked (for the whole
-    // tile) to the pair before it inside its group.  Built by the first wave, one anti-diagonal at a time (an
-    // anti-diagonal has at most 32 pairs).
+    // The stored runs of this 32 x 32 position, in accumulation order: a pair starts a run unless it is linked (for
+    // the whole position) to the pair before it inside its group.  Built by the first wave, one anti-diagonal at a time
+    // (an anti-diagonal has at most 32 pairs).
     if (tid < 64) {
-        const int32_t* dA = a.da + (size_t)tm * a.order.s;
-        const int32_t* dB = a.db + (size_t)tn * a.order.s;
+        const int32_t* dA = a.da + (size_t)(m0 / LINK_ROWS) * a.order.s;
+        const int32_t* dB = a.db + (size_t)(n0 / LINK_ROWS) * a.order.s;
         int count = 0, slot0 = 0;
         for (int g = a.pass.g_hi; g >= a.pass.g_lo; --g) {
             const int len = diag_len(a.order, g);
@@ -109,7 +134,7 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
             if (tid < len) {
                 const int p = diag_first_p(a.order, g) + tid - 1, q = g - p - 2;     // 0-based slice indices
                 const bool first = tid == 0;                                        // first pair of the anti-diagonal: ends every run
-                start = tid % a.order.run_limit == 0 || !(a.allow_chain && pair_linked(dA, dB, p - 1, q + 1));   // stored on its own
+                start = starts_run(a.order, a.allow_chain, dA, dB, tid, p, q);      // stored on its own
                 entry = (uint32_t)(slot0 + tid) | ((uint32_t)p << 12) | ((uint32_t)q << 18) | ((uint32_t)first << 24);
             }
             const unsigned long long mask = __ballot(start);
@@ -122,28 +147,17 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
     __syncthreads();
     const int n_runs = n_entries;
 
-    // Integer-only variant: the sum lives in a RoundedSum, which adds exactly in 64-bit integers for as long as no
-    // rounding can occur and with the emulated FP64 addition from then on.
-    RoundedSum E[4];
-    if constexpr (EMU) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            if (a.read_S) E[r].start_at((uint64_t)S[r]);
-            else E[r].start_at_zero();
-        }
-    }
-    auto add_run = [&](int r, int run_sum, int run_e) {
+    auto add_run = [&](int r, run_t run_sum, int run_e) {
         if (run_sum == 0) return;                                     // adding an exact zero changes nothing
-        if constexpr (EMU) {
-            E[r].add(run_sum, run_e - a.two_b);
-        } else {
-            S[r] = (acc_t)((double)S[r] + ldexp((double)run_sum, run_e - a.two_b));
-        }
+        if constexpr (HW) Sd[r] = Sd[r] + ldexp((double)run_sum, run_e - a.two_b);
+        if constexpr (EMU) E[r].add((int64_t)run_sum, run_e - a.two_b);
+        if constexpr (EXACT) X[r].add((int64_t)run_sum, EXACT_WINDOW_BITS + run_e);      // unit: 2^(-2b - window) of the leading scale
     };
-    // Per element, consecutive stored runs of one anti-diagonal with the same scale are merged further (32-bit
-    // integer, units of 2^-p_frac) before the FP64 addition: together with the tile-wide runs formed by the GEMM
+    // Per element, consecutive stored runs of one anti-diagonal with the same scale are merged further (integer,
+    // units of 2^-p_frac) before the FP64 addition: together with the tile-wide runs formed by the GEMM
     // kernel this is the element-wise rule "consecutive pairs of an anti-diagonal with equal scale are summed exactly".
-    int run_sum[4] = {0, 0, 0, 0}, run_e[4] = {0, 0, 0, 0};
+    run_t run_sum[4] = {0, 0, 0, 0};
+    int run_e[4] = {0, 0, 0, 0};
     auto process = [&](uint32_t entry, const uint4& v) {
         const int p = (entry >> 12) & 63, q = (entry >> 18) & 63;
         const bool first = (entry >> 24) & 1;
@@ -153,8 +167,8 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
         for (int r = 0; r < 4; ++r) {
             const int e = eA + (q == 0 ? 0 : relB[q][nl + r]);
             // the product as an integer in units of 2^-p_frac: exact in FP32 (|integer| <= 2^24), no FP64 involved
-            const int iv = (int)ldexpf(__uint_as_float(vv[r]), a.p_frac);
-            if (!first && e == run_e[r]) {
+            const int iv = PINT ? (int)vv[r] : (int)ldexpf(__uint_as_float(vv[r]), a.p_frac);
+            if (a.merge && !first && e == run_e[r]) {
                 run_sum[r] += iv;
             } else {
                 add_run(r, run_sum[r], run_e[r]);
@@ -178,14 +192,19 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
         }
     }
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        add_run(r, run_sum[r], run_e[r]);
-        if constexpr (EMU) S[r] = (acc_t)E[r].value();
-    }
+    for (int r = 0; r < 4; ++r) add_run(r, run_sum[r], run_e[r]);
 
     if (a.write_S) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) reinterpret_cast<acc_t*>(a.S)[tile_off + r] = S[r];
+        for (int r = 0; r < 4; ++r) {
+            if constexpr (HW) a.S[tile_off + r] = (uint64_t)__double_as_longlong(Sd[r]);
+            if constexpr (EMU) a.S[tile_off + r] = E[r].value();
+            if constexpr (EXACT) {
+                a.S[tile_off + r] = X[r].w0;
+                a.S[pair_stride + tile_off + r] = X[r].w1;
+                a.S[2 * pair_stride + tile_off + r] = X[r].w2;
+            }
+        }
         return;
     }
     const int64_t mi = m0 + ml;
@@ -196,31 +215,67 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
         const int64_t nj = n0 + nl + r;
         if (nj >= a.n) continue;
         const int base = baseA + relB[0][nl + r];
-        acc_t* dst = reinterpret_cast<acc_t*>(a.C) + mi + nj * a.ldc;
-        if constexpr (EMU) {
-            uint64_t v = fp64_scale_pow2_emulated((uint64_t)S[r], base);
-            if (a.add_to_C) v = fp64_add_emulated((uint64_t)*dst, v);
-            *dst = (acc_t)v;
+        if constexpr (HW) {
+            double* dst = a.C + mi + nj * a.ldc;
+            double v = ldexp(Sd[r], base);
+            if (a.add_to_C) v = *dst + v;
+            *dst = v;
         } else {
-            double v = ldexp((double)S[r], base);
-            if (a.add_to_C) v = (double)*dst + v;
-            *dst = (acc_t)v;
+            uint64_t* dst = reinterpret_cast<uint64_t*>(a.C) + mi + nj * a.ldc;
+            uint64_t v;
+            if constexpr (EMU) v = fp64_scale_pow2_emulated(E[r].value(), base);
+            else v = X[r].round_to_fp64(base - a.two_b - EXACT_WINDOW_BITS);
+            if (a.add_to_C) v = fp64_add_emulated(*dst, v);
+            *dst = v;
         }
     }
 }
 
-__global__ void __launch_bounds__(256) export_products_kernel(const float* __restrict__ P, float* __restrict__ out, int64_t m,
-                                                              int64_t n, int tiles_m, int tiles_n, float factor) {
-    // one thread per stored float; grid.y = pair
-    const size_t pair_stride = (size_t)tiles_m * tiles_n * TILE_ELEMS;
-    const int64_t z = blockIdx.y;
-    for (size_t g = (size_t)blockIdx.x * 256 + threadIdx.x; g < pair_stride; g += (size_t)gridDim.x * 256) {
-        const int tile = (int)(g / TILE_ELEMS), idx = (int)(g % TILE_ELEMS);
-        const int tn = tile / tiles_m, tm = tile - tn * tiles_m;
+// Verification export: one thread per stored word; grid.y = pair slot of the pass.  Writes the plain column-major
+// matrices and, if asked, the number of pairs each slot sums for the element (see launch_export_products).
+struct ExportArgs {
+    const float* P;
+    float* out;
+    uint8_t* run_len;
+    int64_t m, n;
+    int tiles_m, tiles_n;
+    float factor;            // FP32 products: the exact power of two that undoes the FP6 code scaling
+    int p_is_int;
+    int allow_chain;
+    const int32_t* da;
+    const int32_t* db;
+    PairOrder order;
+    Pass pass;
+};
+__global__ void __launch_bounds__(256) export_products_kernel(const ExportArgs a) {
+    const size_t pair_stride = (size_t)a.tiles_m * a.tiles_n * TILE_ELEMS;
+    const int z = blockIdx.y;
+    // the pair of slot z: anti-diagonal g, position pos in it
+    int g = a.pass.g_hi, pos = z;
+    for (; g > a.pass.g_lo && pos >= diag_len(a.order, g); --g) pos -= diag_len(a.order, g);
+    const int len = diag_len(a.order, g);
+    const int p = diag_first_p(a.order, g) + pos - 1, q = g - p - 2;      // 0-based slice indices
+    for (size_t gi = (size_t)blockIdx.x * 256 + threadIdx.x; gi < pair_stride; gi += (size_t)gridDim.x * 256) {
+        const int tile = (int)(gi / TILE_ELEMS), idx = (int)(gi % TILE_ELEMS);
+        const int tn = tile / a.tiles_m, tm = tile - tn * a.tiles_m;
         int ml, nl;
         acc_order_to_mn(idx, ml, nl);
         const int64_t mi = (int64_t)tm * TILE + ml, nj = (int64_t)tn * TILE + nl;
-        if (mi < m && nj < n) out[((size_t)z * n + nj) * m + mi] = P[(size_t)z * pair_stride + g] * factor;   // power of two: exact
+        if (mi >= a.m || nj >= a.n) continue;
+        const int32_t* dA = a.da + (size_t)(mi / LINK_ROWS) * a.order.s;
+        const int32_t* dB = a.db + (size_t)(nj / LINK_ROWS) * a.order.s;
+        int run = 0;
+        if (starts_run(a.order, a.allow_chain, dA, dB, pos, p, q)) {
+            run = 1;
+            while (pos + run < len && !starts_run(a.order, a.allow_chain, dA, dB, pos + run, p + run, q - run)) ++run;
+        }
+        const size_t o = ((size_t)z * a.n + nj) * a.m + mi;
+        const uint32_t w = reinterpret_cast<const uint32_t*>(a.P)[(size_t)z * pair_stride + gi];
+        uint32_t* const dst = reinterpret_cast<uint32_t*>(a.out) + o;
+        if (run == 0) *dst = 0u;                                                // all-zero bits either way
+        else if (a.p_is_int) *dst = w;                                          // the INT32 word, bit for bit
+        else *dst = __float_as_uint(__uint_as_float(w) * a.factor);             // power of two: exact
+        if (a.run_len) a.run_len[o] = (uint8_t)run;
     }
 }
 
@@ -267,8 +322,8 @@ unsigned grid_for(int64_t work_items) {
 }  // namespace
 
 hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B, const PairOrder& order, const Pass& ps,
-                             bool first_pass, bool last_pass, int64_t t, const float* P, double* S_io,
-                             double* C, int64_t ldc, int accum_mode, hipStream_t st) {
+                             bool first_pass, bool last_pass, int64_t t, const float* P, uint64_t* S_io,
+                             double* C, int64_t ldc, int accum_mode, int sum_rule, bool chained, hipStream_t st) {
     if (pl.tiles_m == 0 || pl.tiles_n == 0) return hipSuccess;
     AccArgs a;
     a.P = P; a.S = S_io; a.C = C; a.ldc = ldc;
@@ -278,25 +333,43 @@ hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B,
     a.m = pl.m; a.n = pl.n; a.tiles_m = (int)pl.tiles_m; a.tiles_n = (int)pl.tiles_n;
     a.two_b = 2 * pl.b;
     a.p_frac = pl.p_frac;
-    a.allow_chain = 1;
-    a.da = A.deltas + (size_t)t * pl.tiles_m * pl.s;
-    a.db = B.deltas + (size_t)t * pl.tiles_n * pl.s;
+    a.allow_chain = chained ? 1 : 0;
+    a.merge = (sum_rule == SUM_RUNS || accum_mode == ACC_EXACT) ? 1 : 0;
+    a.da = A.deltas + (size_t)t * (A.rows_pad / LINK_ROWS) * pl.s;
+    a.db = B.deltas + (size_t)t * (B.rows_pad / LINK_ROWS) * pl.s;
     a.order = order; a.pass = ps;
     a.read_S = !first_pass;
     a.write_S = !last_pass;
     a.add_to_C = t > 0;
     const int64_t blocks = pl.tiles_m * pl.tiles_n * 64;
     if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
-    if (accum_mode == 1) hipLaunchKernelGGL((accumulate_kernel<true>), dim3((unsigned)blocks), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((accumulate_kernel<false>), dim3((unsigned)blocks), dim3(256), 0, st, a);
+    const dim3 grid((unsigned)blocks), block(256);
+    if (pl.p_is_int) {
+        if (accum_mode == ACC_EXACT) hipLaunchKernelGGL((accumulate_kernel<ACC_EXACT, true>), grid, block, 0, st, a);
+        else if (accum_mode == ACC_EMU) hipLaunchKernelGGL((accumulate_kernel<ACC_EMU, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((accumulate_kernel<ACC_HW, true>), grid, block, 0, st, a);
+    } else {
+        if (accum_mode == ACC_EXACT) hipLaunchKernelGGL((accumulate_kernel<ACC_EXACT, false>), grid, block, 0, st, a);
+        else if (accum_mode == ACC_EMU) hipLaunchKernelGGL((accumulate_kernel<ACC_EMU, false>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((accumulate_kernel<ACC_HW, false>), grid, block, 0, st, a);
+    }
     return hipGetLastError();
 }
 
-hipError_t launch_export_products(const Plan& pl, int nz, const float* P, float* out, hipStream_t st) {
-    if (nz <= 0 || pl.m == 0 || pl.n == 0) return hipSuccess;
-    dim3 grid(grid_for(pl.tiles_m * pl.tiles_n * (int64_t)TILE_ELEMS), (unsigned)nz);
-    const float factor = ldexpf(1.0f, pl.p_frac - 2 * pl.b);
-    hipLaunchKernelGGL(export_products_kernel, grid, dim3(256), 0, st, P, out, pl.m, pl.n, (int)pl.tiles_m, (int)pl.tiles_n, factor);
+hipError_t launch_export_products(const Plan& pl, const Operand& A, const Operand& B, const PairOrder& order, const Pass& ps,
+                                  bool chained, int64_t t, const float* P, float* out, uint8_t* run_len_out, hipStream_t st) {
+    if (ps.npairs <= 0 || pl.m == 0 || pl.n == 0) return hipSuccess;
+    ExportArgs a;
+    a.P = P; a.out = out; a.run_len = run_len_out;
+    a.m = pl.m; a.n = pl.n; a.tiles_m = (int)pl.tiles_m; a.tiles_n = (int)pl.tiles_n;
+    a.factor = ldexpf(1.0f, pl.p_is_int ? 0 : pl.p_frac - 2 * pl.b);
+    a.p_is_int = pl.p_is_int;
+    a.allow_chain = chained ? 1 : 0;
+    a.da = A.deltas + (size_t)t * (A.rows_pad / LINK_ROWS) * pl.s;
+    a.db = B.deltas + (size_t)t * (B.rows_pad / LINK_ROWS) * pl.s;
+    a.order = order; a.pass = ps;
+    dim3 grid(grid_for(pl.tiles_m * pl.tiles_n * (int64_t)TILE_ELEMS), (unsigned)ps.npairs);
+    hipLaunchKernelGGL(export_products_kernel, grid, dim3(256), 0, st, a);
     return hipGetLastError();
 }
 

@@ -130,7 +130,7 @@ OZAKI_HD uint64_t int53_scaled_to_fp64(int64_t n, int e2) {
     return sign | ((uint64_t)e << 52) | ((a << (52 - top)) & F64_FRAC);
 }
 
-// A running FP64 sum of terms v * 2^e2 (v a 32-bit integer), each addition rounded to nearest even.  As long as the sum
+// A running FP64 sum of terms v * 2^e2 (v an integer below 2^52 in magnitude), each addition rounded to nearest even.  As long as the sum
 // and the next term fit together into 53 bits (both below 2^52 in units of the smaller of their two scales) the
 // rounded addition is exact, so the sum is held as a 64-bit integer x * 2^ex and an addition is a shift and an
 // integer add; the first addition that may round turns the sum into FP64 bits once and fp64_add_emulated takes over.
@@ -143,16 +143,16 @@ struct RoundedSum {
     OZAKI_HD bool exact() const { return ex != NOT_EXACT; }
     OZAKI_HD void start_at_zero() { w = 0; ex = 0; }
     OZAKI_HD void start_at(uint64_t fp64_bits) { w = fp64_bits; ex = NOT_EXACT; }
-    OZAKI_HD void add(int v, int e2) {
+    OZAKI_HD void add(int64_t v, int e2) {
         if (v == 0) return;                                     // adding an exact zero changes nothing
         if (exact()) {
             const int64_t x = (int64_t)w;
-            if (x == 0) { w = (uint64_t)(int64_t)v; ex = e2; return; }
+            if (x == 0) { w = (uint64_t)v; ex = e2; return; }
             const int lo = ex < e2 ? ex : e2, sx = ex - lo, sv = e2 - lo;
             const uint64_t ax = (uint64_t)(x < 0 ? -x : x);
-            const uint64_t av = (uint64_t)(v < 0 ? -(int64_t)v : (int64_t)v);
+            const uint64_t av = (uint64_t)(v < 0 ? -v : v);
             if (64 - clz64(ax) + sx <= 52 && 64 - clz64(av) + sv <= 52) {
-                w = (w << sx) + ((uint64_t)(int64_t)v << sv);
+                w = (w << sx) + ((uint64_t)v << sv);
                 ex = lo;
                 return;
             }
@@ -162,6 +162,80 @@ struct RoundedSum {
         w = fp64_add_emulated(w, int53_scaled_to_fp64(v, e2));
     }
     OZAKI_HD uint64_t value() const { return exact() ? int53_scaled_to_fp64((int64_t)w, ex) : w; }
+};
+
+// A 192-bit two's-complement fixed-point accumulator: the exact sum of terms v * 2^sh units (v an integer of at most
+// 2^36 in magnitude, sh <= 144), rounded to FP64 once at the end.  1024 such terms stay below 2^190: no overflow.
+struct Fixed192 {
+    uint64_t w0, w1, w2;                                        // least significant word first
+
+    OZAKI_HD void clear() { w0 = w1 = w2 = 0; }
+    // += v * 2^sh.  A negative sh cuts the term to whole units towards minus infinity (arithmetic shift).
+    OZAKI_HD void add(int64_t v, int sh) {
+        if (sh < 0) {
+            v >>= (sh < -63 ? 63 : -sh);
+            sh = 0;
+        }
+        const int word = sh >> 6, bit = sh & 63;
+        const uint64_t lo = (uint64_t)v << bit;
+        const uint64_t hi = (uint64_t)((v >> 1) >> (63 - bit));      // bits 64.. of the shifted value, sign-extended
+        const uint64_t ext = (uint64_t)(v >> 63);                    // all sign bits
+        // the addend as three words, placed by the word index without branching
+        const uint64_t a0 = word == 0 ? lo : 0;
+        const uint64_t a1 = word == 0 ? hi : word == 1 ? lo : 0;
+        const uint64_t a2 = word == 0 ? ext : word == 1 ? hi : lo;
+        const uint64_t s0 = w0 + a0;
+        const uint64_t c0 = s0 < a0;
+        const uint64_t t1 = w1 + a1;
+        const uint64_t c1 = t1 < a1;
+        const uint64_t s1 = t1 + c0;
+        const uint64_t c1b = s1 < c0;
+        w0 = s0;
+        w1 = s1;
+        w2 = w2 + a2 + c1 + c1b;
+    }
+    // The sum times 2^unit_e2, rounded to the nearest FP64 value, ties to even; flushed / saturated outside the normal
+    // range like the other routines of this header.
+    OZAKI_HD uint64_t round_to_fp64(int unit_e2) const {
+        uint64_t m0 = w0, m1 = w1, m2 = w2;
+        const uint64_t sign = m2 & F64_SIGN;
+        if (sign) {                                                 // magnitude = two's complement negation
+            m0 = ~m0 + 1;
+            const uint64_t c = m0 == 0;
+            m1 = ~m1 + c;
+            m2 = ~m2 + ((c != 0 && m1 == 0) ? 1 : 0);
+        }
+        if ((m0 | m1 | m2) == 0) return 0;
+        const int top = m2 ? 191 - clz64(m2) : m1 ? 127 - clz64(m1) : 63 - clz64(m0);     // leading one
+        uint64_t sig;
+        if (top <= 52) {
+            sig = m0 << (52 - top);                                 // short enough: exact
+        } else {
+            // the 55 bits from the leading one down (53 of the significand, a guard bit, one more), then sticky
+            const int r = top - 54;                                 // bits below those 55; may be negative (top 53, 54)
+            uint64_t head;
+            bool sticky;
+            if (r <= 0) {
+                head = m0 << (-r);
+                sticky = false;
+            } else {
+                const int word = r >> 6, bit = r & 63;
+                const uint64_t x0 = word == 0 ? m0 : word == 1 ? m1 : m2;
+                const uint64_t x1 = word == 0 ? m1 : word == 1 ? m2 : 0;
+                head = bit ? (x0 >> bit) | (x1 << (64 - bit)) : x0;
+                const uint64_t below = bit ? (x0 << (64 - bit)) : 0;
+                sticky = below != 0 || (word >= 1 && m0 != 0) || (word == 2 && m1 != 0);
+            }
+            sig = head >> 2;                                        // 53 bits, leading one at position 52
+            const unsigned guard = (unsigned)(head >> 1) & 1u, rest = ((unsigned)head & 1u) | (sticky ? 1u : 0u);
+            sig += guard & (rest | (unsigned)(sig & 1));            // a carry to 2^53 bumps the exponent below
+        }
+        const int e = 1023 + top + unit_e2;
+        if (e <= 0) return sign;
+        const uint64_t rbits = ((uint64_t)e << 52) + (sig - F64_HIDDEN);
+        if (rbits >= F64_INF) return sign | F64_INF;
+        return sign | rbits;
+    }
 };
 
 // x * 2^e2 on FP64 bits (zeros stay zeros; the result is flushed / saturated outside the normal range).

@@ -8,7 +8,7 @@ namespace ozaki {
 
 constexpr int MAX_SLICES = 32;
 constexpr int MAX_PAIRS = MAX_SLICES * MAX_SLICES;      // all s*s pairs in the full mode
-constexpr int64_t MAX_K_BLOCK = 32768;
+constexpr int64_t MAX_K_BLOCK_IN_REGISTERS = 16384;     // longer blocks are sliced by the streaming kernel (state in work memory)
 
 // ---- tiling of the slice-pair GEMM: one workgroup computes one TILE x TILE block of one pair product ------
 constexpr int TILE = 256;
@@ -17,8 +17,17 @@ constexpr int CHUNK_BYTES_FP6 = 48;       // the same 64 inner indices as 6-bit 
 constexpr int TILE_ELEMS = TILE * TILE;
 
 // slice formats (values of ozaki_slice_format)
-constexpr int FMT_FP8 = 0, FMT_FP16 = 1, FMT_FP6 = 2, FMT_FP6_E3M2 = 3;     // FMT_FP6 is E2M3
+constexpr int FMT_FP8 = 0, FMT_FP16 = 1, FMT_FP6 = 2, FMT_FP6_E3M2 = 3, FMT_INT8 = 4;     // FMT_FP6 is E2M3
 __host__ __device__ constexpr bool fmt_is_fp6(int fmt) { return fmt == FMT_FP6 || fmt == FMT_FP6_E3M2; }
+
+// how the slice-pair products of a block are summed (values of the accum_mode / sum_rule arguments)
+constexpr int ACC_HW = 0, ACC_EMU = 1, ACC_EXACT = 2;
+constexpr int SUM_RUNS = 0, SUM_PLAIN = 1;
+
+// "exact" accumulation: the block sum of an element is a 192-bit two's-complement integer in units of
+// 2^(cA_1 + cB_1 - 2b - EXACT_WINDOW_BITS); at most 1024 terms of at most 2^36 units * 2^EXACT_WINDOW_BITS each.
+constexpr int EXACT_WINDOW_BITS = 144;
+constexpr int SUM_WORDS_MAX = 3;          // 64-bit words of a running block sum kept in work memory between passes
 
 // ---- slice storage ---------------------------------------------------------------------------------------
 // One slice matrix (block t, slice p) of an operand is stored as [chunk kc][vector r][CHUNK_BYTES]:
@@ -37,9 +46,12 @@ struct Operand {
     int64_t rows_pad;     // multiple of TILE
     uint8_t* slices;      // [T][s][chunks][rows_pad][row_bytes]
     int32_t* exps;        // [T][s][rows_pad]   exponent c of Eq. 4 (0 for padding vectors)
-    int32_t* deltas;      // [T][rows_pad/TILE][s]  per 256-vector tile and slice p: c_p - c_(p+1) if that difference
-                          //                        is the same for all real vectors of the tile, else DELTA_IRREGULAR
+    int32_t* deltas;      // [T][rows_pad/LINK_ROWS][s]  per group of 32 vectors (one matrix-unit tile edge) and slice p:
+                          //                        c_p - c_(p+1) if that difference is the same for all real vectors of
+                          //                        the group, else DELTA_IRREGULAR
 };
+
+constexpr int LINK_ROWS = 32;             // granularity of the equal-scale decision: one 32 x 32 matrix-unit tile
 
 constexpr int DELTA_IRREGULAR = -2147483647 - 1;
 
@@ -58,10 +70,12 @@ struct Plan {
     int64_t chunks;       // chunks per block
     int full;             // 1: all s*s pairs, 0: the pairs with p + q <= s + 1
     int npairs;           // s(s+1)/2 or s*s
-    int run_limit;        // floor(2^24 / (kb * 4^b)): equal-scale pair products that may be summed exactly in FP32
+    int run_limit;        // floor(window / (kb * 4^b)): equal-scale pair products that may be summed exactly in the
+                          // matrix unit's accumulators (window 2^24 for FP32, 2^31 - 1 for INT32)
     int group_len;        // pairs per group of the GEMM kernel, <= run_limit (PairOrder::run_limit of the launches)
     int64_t tiles_m, tiles_n;
     int64_t m_pad, n_pad;
+    int p_is_int;         // 1: the stored products are INT32 words (INT8 slices), 0: FP32
 };
 
 // The slice pairs (p, q), 1-based, and their accumulation order: anti-diagonals g = p + q from the least
@@ -120,10 +134,10 @@ __host__ __device__ inline Group pass_group(const PairOrder& o, const Pass& ps, 
     return Group{1, 1, 0, 0};
 }
 
-// True if, for every element of the tile, pair (p+1, q-1) carries the same scale factor 2^(cA + cB) as pair
-// (p, q) (0-based slice indices): then the two products can be summed in the FP32 accumulator of the matrix unit
-// (a group has at most run_limit pairs, so the sum stays inside the exact window).  dA / dB: the tile's rows of
-// Operand::deltas.
+// True if, for every element of a 32 x 32 tile, pair (p+1, q-1) carries the same scale factor 2^(cA + cB) as pair
+// (p, q) (0-based slice indices): then the two products can be summed in the accumulator of the matrix unit
+// (a group has at most run_limit pairs, so the sum stays inside the exact window).  dA / dB: the rows of
+// Operand::deltas of the tile's 32 rows of A and 32 columns of B.
 __host__ __device__ inline bool pair_linked(const int32_t* dA, const int32_t* dB, int p, int q) {
     const int a = dA[p], b = dB[q - 1];
     return a != DELTA_IRREGULAR && a == b;
@@ -148,13 +162,16 @@ __host__ __device__ inline void acc_order_to_mn(int idx, int& m_in_tile, int& n_
 hipError_t launch_transpose(const double* A, int64_t lda, int64_t m, int64_t k, double* At, hipStream_t st);
 
 // Vectors are contiguous: vector r of an operand starts at X + r*ldv and has k entries.  Writes the internal layout of
-// up to two operands in one launch (a null Operand, or one without vectors, is skipped).
+// up to two operands in one launch (a null Operand, or one without vectors, is skipped).  Blocks longer than
+// MAX_K_BLOCK_IN_REGISTERS are sliced by a streaming kernel that keeps its per-element state in `long_state`
+// (split_state_bytes(pl) bytes; may be null otherwise).
 hipError_t launch_split(const double* X0, int64_t ldv0, const Operand* op0, const double* X1, int64_t ldv1, const Operand* op1,
-                        const Plan& pl, int* flags, hipStream_t st);
+                        const Plan& pl, int* flags, void* long_state, hipStream_t st);
+size_t split_state_bytes(const Plan& pl, int64_t rows_a, int64_t rows_b);
 
 // Slices until every remainder is zero (paragraph before Eq. 4): atomicMax of the per-vector count into flags[1]
 // (which the caller has cleared); MAX_SLICES + 1 means that MAX_SLICES slices do not exhaust some vector.
-hipError_t launch_count_slices(const double* X, int64_t ldv, const Plan& pl, int64_t rows, int* flags, hipStream_t st);
+hipError_t launch_count_slices(const double* X, int64_t ldv, const Plan& pl, int64_t rows, int* flags, void* long_state, hipStream_t st);
 
 // Internal layout -> plain vector-major codes (verification export).
 hipError_t launch_export_slices(const Plan& pl, const Operand& op, void* out, hipStream_t st);
@@ -169,14 +186,20 @@ hipError_t launch_pair_gemm(const Plan& pl, const Operand& A, const Operand& B, 
                             bool allow_chain, int64_t t, float* P, hipStream_t st);
 
 // Accumulate the pairs of pass `ps` of block t.  S_io: running block sum in accumulator order (read unless the
-// pass is the block's first, written unless it is the last).  On the last pass the block sum is rescaled by the
-// first-slice exponents and stored to C (t == 0) or added to C (t > 0).
+// pass is the block's first, written unless it is the last): one 64-bit word per element (FP64 bits), three in the
+// exact mode, word w of element e at S_io[w * tiles * TILE_ELEMS + e].  On the last pass the block sum is rescaled by
+// the first-slice exponents and stored to C (t == 0) or added to C (t > 0).  `chained`: the products were written
+// with allow_chain.  sum_rule SUM_PLAIN: every product is added on its own.
 hipError_t launch_accumulate(const Plan& pl, const Operand& A, const Operand& B, const PairOrder& order, const Pass& ps,
-                             bool first_pass, bool last_pass, int64_t t, const float* P, double* S_io,
-                             double* C, int64_t ldc, int accum_mode, hipStream_t st);
+                             bool first_pass, bool last_pass, int64_t t, const float* P, uint64_t* S_io,
+                             double* C, int64_t ldc, int accum_mode, int sum_rule, bool chained, hipStream_t st);
 
-// P in accumulator order -> [nz][n][m] column-major matrices (verification export).
-hipError_t launch_export_products(const Plan& pl, int nz, const float* P, float* out, hipStream_t st);
+// P in accumulator order -> [nz][n][m] column-major matrices (verification export): FP32 values of Eq. 10-11, or INT32
+// integers for INT8 slices.  run_len_out (may be null): for every element and pair slot of the pass, how many pairs'
+// products the slot holds summed (1 without chaining; 0: the pair's product is part of an earlier slot's sum, and
+// `out` gets 0 there).
+hipError_t launch_export_products(const Plan& pl, const Operand& A, const Operand& B, const PairOrder& order, const Pass& ps,
+                                  bool chained, int64_t t, const float* P, float* out, uint8_t* run_len_out, hipStream_t st);
 
 // C = alpha * W + beta * C element by element (one rounding per operation, no fused multiply-add; beta == 0: C is not
 // read), W and C column-major m x n.

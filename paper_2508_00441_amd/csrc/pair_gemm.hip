@@ -3,15 +3,19 @@
 // For one k-block and one slice pair (p, q) the product  P[i][j] = sum_kk sliceA_p[i][kk] * sliceB_q[j][kk]
 // is formed with FP8 or FP6 (v_mfma_f32_32x32x64_f8f6f4; FP6 codes hold twice the slice value, which the
 // accumulation kernel undoes with the exponents) or FP16 (v_mfma_f32_32x32x16_f16) inputs and FP32
-// accumulation.  Every slice entry is q*2^-b with |q| <= 2^b and k_block*4^b <= 2^24, so every partial sum
+// accumulation, or with INT8 inputs and INT32 accumulation (v_mfma_i32_32x32x32_i8; the slice entries are then the
+// integers q themselves and the sums are exact up to 2^31 - 1).  Every slice entry is q*2^-b with |q| <= 2^b and k_block*4^b <= 2^24, so every partial sum
 // is an integer multiple of 2^-2b below 2^(24-2b) in magnitude and the FP32 accumulation is exact (Eq. 11).
 // Because the sum is exact, the order in which the inner index is consumed is irrelevant; the kernel
 // feeds both operands with the same (arbitrary but identical) assignment of inner indices to lanes.
 //
 // Work decomposition: one workgroup of four waves (one per SIMD) computes a 256 x 256 block of P for one
-// group of pairs (consecutive pairs of an anti-diagonal, streamed through one continuous pipeline; products
-// that carry the same scale factor for the whole tile are summed in the accumulators and stored once, which
-// is exact because a group never exceeds the FP32 window of Eq. 11); each wave owns 128 x 128 (4 x 4 MFMA tiles of 32 x 32, 256 accumulator registers per lane).  The
+// group of pairs (consecutive pairs of an anti-diagonal, streamed through one continuous pipeline); each wave owns
+// 128 x 128 (4 x 4 MFMA tiles of 32 x 32, 256 accumulator registers per lane).  Whether the product of the next pair
+// keeps accumulating on top of the current one is decided per 32 x 32 MFMA tile: it does where all 32 rows of A and all
+// 32 columns of B concerned carry the same scale factor for both pairs (exact, because a group never exceeds the
+// window of Eq. 11); a tile that does not is stored and cleared, so one irregular row costs one 4 KiB store, not the
+// workgroup's 256 KiB.  The
 // matrix unit's "row" operand is the B slice (index n), its "column" operand the A slice (index m), so that
 // the lanes of a wave run along m, the contiguous direction of column-major C.
 //
@@ -45,6 +49,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef int v16i __attribute__((ext_vector_type(16)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 
 struct GemmArgs {
@@ -55,8 +60,8 @@ struct GemmArgs {
     int64_t chunks;
     int tiles_m, tiles_n;
     int allow_chain;
-    const int32_t* da;       // A deltas of the block: [tiles_m][s]
-    const int32_t* db;       // B deltas of the block: [tiles_n][s]
+    const int32_t* da;       // A deltas of the block: [rows_pad_a / 32][s]
+    const int32_t* db;       // B deltas of the block: [rows_pad_b / 32][s]
     PairOrder order;
     Pass pass;
 };
@@ -81,6 +86,8 @@ __device__ __forceinline__ void wait_and_barrier() {
 template <int FMT>
 __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
     constexpr bool FP16 = FMT == FMT_FP16;
+    constexpr bool INT8 = FMT == FMT_INT8;
+    constexpr bool HALF = FP16 || INT8;               // 16-byte fragments, two k-steps per 64-byte stage
     constexpr bool FP6 = fmt_is_fp6(FMT);
     constexpr int FP6_CODE = FMT == FMT_FP6_E3M2 ? 3 : 2;     // operand format field of the instruction: 2 = E2M3, 3 = E3M2
     constexpr int BK = FP6 ? CHUNK_BYTES_FP6 : CHUNK_BYTES;   // bytes of the inner dimension per vector and stage
@@ -88,8 +95,8 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
     constexpr int STAGE_BYTES = 2 * OPERAND_BYTES;    // X tile + Y tile
     constexpr int LPW = OPERAND_BYTES / 1024 / 4;     // direct-to-LDS load instructions per wave, operand and stage
     constexpr int NSTAGE = FP6 ? 6 : 5;               // ring of stage buffers: 5 x 32 KiB resp. 6 x 24 KiB of the 160 KiB LDS
-    constexpr int KS = FP16 ? 2 : 1;                  // MFMA k-steps per stage (32 resp. 64 inner indices each)
-    constexpr int READS = FP16 ? 8 : 16;              // LDS read instructions per wave and k-step
+    constexpr int KS = HALF ? 2 : 1;                  // MFMA k-steps per stage (half a stage's bytes, or all of them, each)
+    constexpr int READS = HALF ? 8 : 16;              // LDS read instructions per wave and k-step
     __shared__ __attribute__((aligned(16))) uint8_t lds[NSTAGE * STAGE_BYTES];
 
     const int tid = threadIdx.x;
@@ -105,15 +112,33 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
     const Group grp = pass_group(a.order, a.pass, gi);
     const int glen = grp.len, p0 = grp.p0 - 1, q0 = grp.q0 - 1;       // 0-based slice indices from here on
     const int chunks = (int)a.chunks;
-    // bit j of `links`: pair j+1 of the group carries, for every element of this tile, the same scale factor as
-    // pair j, so its product keeps accumulating on top of pair j's (the sum stays inside the exact FP32 window
-    // because a group has at most run_limit pairs); otherwise the accumulators are stored and cleared in between
-    unsigned links = 0;
-    if (a.allow_chain) {
-        const int32_t* dA = a.da + (size_t)tm * a.order.s;
-        const int32_t* dB = a.db + (size_t)tn * a.order.s;
-        for (int j = 0; j + 1 < glen; ++j) links |= pair_linked(dA, dB, p0 + j, q0 - j) ? (1u << j) : 0u;
-    }
+    // Whether pair jp+1 of the group keeps accumulating on top of pair jp is decided per MFMA tile (i, j) of the wave,
+    // when pair jp is complete: it does if all 32 rows of A and all 32 columns of B behind the tile carry the same scale
+    // factor for both pairs (pair_linked; the sum stays inside the exact window because a group has at most run_limit
+    // pairs).  The rows of A behind tile column j are the 32-vector group tm*8 + wm*4 + j, the columns of B behind
+    // tile row i the group tn*8 + wn*4 + i.  The delta rows are read through the scalar cache (they were written by an
+    // earlier kernel and the addresses are wave-uniform), so they stay out of the vector-memory counter that paces
+    // the load ring.
+    typedef const __attribute__((address_space(4))) int32_t* delta_ptr;
+    const int nslices = a.order.s;
+    const delta_ptr dA = (delta_ptr)(a.da + (size_t)(tm * 8 + wm * 4) * nslices);
+    const delta_ptr dB = (delta_ptr)(a.db + (size_t)(tn * 8 + wn * 4) * nslices);
+    // bit i*4+j: tile (i, j) continues its run after pair jp (0-based position in the group)
+    auto continue_mask = [&](int jp) -> unsigned {
+        if (!a.allow_chain) return 0u;
+        int dav[4], dbv[4];
+#pragma unroll
+        for (int t4 = 0; t4 < 4; ++t4) {
+            dav[t4] = __builtin_amdgcn_readfirstlane(dA[t4 * nslices + p0 + jp]);
+            dbv[t4] = __builtin_amdgcn_readfirstlane(dB[t4 * nslices + q0 - jp - 1]);
+        }
+        unsigned cont = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) cont |= (dav[j] != DELTA_IRREGULAR && dav[j] == dbv[i]) ? (1u << (i * 4 + j)) : 0u;
+        return cont;
+    };
 
     // loader.  FP8/FP16: a wave instruction fills 16 consecutive LDS rows; lane -> row lane/4, physical piece lane%4,
     // which must hold logical piece (lane%4) ^ ((row>>2)&3); the row group starts at a multiple of 16 rows; a wave's
@@ -154,26 +179,21 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
     const int xbase = xrow * BK;
     const int ybase = OPERAND_BYTES + yrow * BK;
 
-    v16f acc[4][4];
-    auto zero_acc = [&]() {
+    typedef typename std::conditional<INT8, v16i, v16f>::type acc_t;      // INT32 or FP32 accumulators
+    typedef typename std::conditional<INT8, v4i, v4f>::type acc4_t;
+    acc_t acc[4][4];
+    auto zero_tile = [&](acc_t& t) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+        for (int r = 0; r < 16; ++r) t[r] = 0;
     };
-    auto store_acc = [&](int slot) {
+    // the wave's part of the product slot `slot`, MFMA tile (i, j): 4 KiB contiguous, 16 bytes per lane and quarter
+    auto store_tile = [&](int slot, int i, int j, const acc_t& t) {
         float* out = a.P + ((size_t)(slot * a.tiles_n + tn) * a.tiles_m + tm) * TILE_ELEMS + (size_t)wave * 16384 + lane * 4;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    v4f v = {acc[i][j][4 * g4], acc[i][j][4 * g4 + 1], acc[i][j][4 * g4 + 2], acc[i][j][4 * g4 + 3]};
-                    *reinterpret_cast<v4f*>(out + ((i * 4 + j) * 4 + g4) * 256) = v;
-                }
+        for (int g4 = 0; g4 < 4; ++g4) {
+            acc4_t v = {t[4 * g4], t[4 * g4 + 1], t[4 * g4 + 2], t[4 * g4 + 3]};
+            *reinterpret_cast<acc4_t*>(out + ((i * 4 + j) * 4 + g4) * 256) = v;
+        }
     };
 
     // The group's pairs are streamed as one sequence of glen * chunks stages.  The A slices p0, p0+1, ... lie back
@@ -205,16 +225,16 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
         issue_kc = adv ? (wrap ? 0 : issue_kc + 1) : issue_kc;
     };
 
-    typedef typename std::conditional<FP16, v8h, v8i>::type frag_t;
+    typedef typename std::conditional<FP16, v8h, typename std::conditional<INT8, v4i, v8i>::type>::type frag_t;
     frag_t xf[2][4], yf[2][4];
     auto read_frags = [&](int stage, int ks, int fb) {
         const uint8_t* base = lds + ((unsigned)stage % NSTAGE) * STAGE_BYTES;
-        if constexpr (FP16) {
+        if constexpr (HALF) {
             const int c0 = ((2 * ks + fg) ^ fsw) << 4;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) xf[fb][i] = *reinterpret_cast<const v8h*>(base + xbase + i * 32 * BK + c0);
+            for (int i = 0; i < 4; ++i) xf[fb][i] = *reinterpret_cast<const frag_t*>(base + xbase + i * 32 * BK + c0);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) yf[fb][j] = *reinterpret_cast<const v8h*>(base + ybase + j * 32 * BK + c0);
+            for (int j = 0; j < 4; ++j) yf[fb][j] = *reinterpret_cast<const frag_t*>(base + ybase + j * 32 * BK + c0);
         } else if constexpr (FP6) {
             // 24 bytes per lane: 16 from the 16-byte plane of its k-group, 8 from the 8-byte plane; the last two
             // registers of the operand are not read by the instruction for 6-bit formats
@@ -259,12 +279,16 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
             for (int jj = 0; jj < 4; ++jj) {
                 const int j = (i & 1) ? 3 - jj : jj;      // boustrophedon: consecutive MFMAs differ in one operand only
                 if constexpr (FP16) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf[fb][i], yf[fb][j], acc[i][j], 0, 0, 0);
+                else if constexpr (INT8) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xf[fb][i], yf[fb][j], acc[i][j], 0, 0, 0);
                 else if constexpr (FP6) acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xf[fb][i], yf[fb][j], acc[i][j], FP6_CODE, FP6_CODE, 0, 0, 0, 0);
                 else acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(xf[fb][i], yf[fb][j], acc[i][j], 0, 0, 0, 0, 0, 0);
             }
     };
 
-    zero_acc();
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) zero_tile(acc[i][j]);
     // prologue: fill the ring, wait for stage 0, read its first fragments
 #pragma unroll
     for (int st = 0; st < NSTAGE; ++st) issue_next(st);
@@ -299,7 +323,7 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
     };
     const std::integral_constant<int, 0> c0;
     const std::integral_constant<int, 1> c1;
-    int run_start = 0;
+    unsigned run_start[4] = {0u, 0u, 0u, 0u};           // byte j of word i: first pair of the run tile (i, j) is accumulating
     for (int jp = 0; jp < glen; ++jp) {
         if constexpr (KS == 1) {
             int c = 0;
@@ -323,13 +347,20 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
                 kstep(c1, c1);
             }
         }
-        // The pair is complete.  If the next pair does not continue the run, store the accumulators to the slot of
-        // the run's first pair and clear them (the stores only make the next vmcnt wait stricter).
+        // The pair is complete.  Every tile whose run the next pair does not continue is stored to the slot of the
+        // run's first pair and cleared (the stores only make the next vmcnt wait stricter).
         const bool last_pair = jp + 1 == glen;
-        if (last_pair || !((links >> jp) & 1u)) {
-            store_acc(grp.slot + run_start);
-            if (!last_pair) zero_acc();
-            run_start = jp + 1;
+        const unsigned cont = last_pair ? 0u : continue_mask(jp);
+        if (cont != 0xFFFFu) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (!((cont >> (i * 4 + j)) & 1u)) {
+                        store_tile(grp.slot + (int)((run_start[i] >> (8 * j)) & 0xFFu), i, j, acc[i][j]);
+                        if (!last_pair) zero_tile(acc[i][j]);
+                        run_start[i] = (run_start[i] & ~(0xFFu << (8 * j))) | ((unsigned)(jp + 1) << (8 * j));
+                    }
         }
     }
 
@@ -353,14 +384,15 @@ hipError_t launch_pair_gemm(const Plan& pl, const Operand& A, const Operand& B, 
     a.rows_pad_a = A.rows_pad; a.rows_pad_b = B.rows_pad; a.chunks = pl.chunks;
     a.tiles_m = (int)pl.tiles_m; a.tiles_n = (int)pl.tiles_n;
     a.allow_chain = allow_chain ? 1 : 0;
-    a.da = A.deltas + (size_t)t * pl.tiles_m * pl.s;
-    a.db = B.deltas + (size_t)t * pl.tiles_n * pl.s;
+    a.da = A.deltas + (size_t)t * (A.rows_pad / LINK_ROWS) * pl.s;
+    a.db = B.deltas + (size_t)t * (B.rows_pad / LINK_ROWS) * pl.s;
     a.order = order; a.pass = ps;
     const int64_t blocks = (int64_t)ps.ngroups * pl.tiles_m * pl.tiles_n;
     if (blocks > 0x7FFFFFFF || pl.chunks > 0x7FFFFFFF) return hipErrorInvalidValue;
     if (pl.fmt == FMT_FP16) hipLaunchKernelGGL((pair_gemm_kernel<FMT_FP16>), dim3((unsigned)blocks), dim3(256), 0, st, a);
     else if (pl.fmt == FMT_FP6) hipLaunchKernelGGL((pair_gemm_kernel<FMT_FP6>), dim3((unsigned)blocks), dim3(256), 0, st, a);
     else if (pl.fmt == FMT_FP6_E3M2) hipLaunchKernelGGL((pair_gemm_kernel<FMT_FP6_E3M2>), dim3((unsigned)blocks), dim3(256), 0, st, a);
+    else if (pl.fmt == FMT_INT8) hipLaunchKernelGGL((pair_gemm_kernel<FMT_INT8>), dim3((unsigned)blocks), dim3(256), 0, st, a);
     else hipLaunchKernelGGL((pair_gemm_kernel<FMT_FP8>), dim3((unsigned)blocks), dim3(256), 0, st, a);
     return hipGetLastError();
 }

@@ -68,10 +68,11 @@ constexpr int NO_ELEM = -(1 << 30);
 // Type2 codes of the two values q0 * 2^-b and q1 * 2^-b (|q| <= 2^b), packed low/high.  The hardware FP32 -> FP8
 // (OCP E4M3 on gfx950) and FP32 -> FP16 conversions are exact here because every such value is a normal number of
 // the format; FP32 arithmetic is not FP64 arithmetic, so the integer-only property of the slicer is about FP64.
-template <bool FP16>
+template <int FMT>
 __device__ __forceinline__ uint32_t encode_type2_pair(int q0, int q1, int b) {
+    if (FMT == FMT_INT8) return ((uint32_t)q0 & 0xFFu) | (((uint32_t)q1 & 0xFFu) << 8);     // the integers themselves, |q| <= 64
     const float f0 = ldexpf((float)q0, -b), f1 = ldexpf((float)q1, -b);
-    if (FP16) {
+    if (FMT == FMT_FP16) {
         typedef _Float16 h2 __attribute__((ext_vector_type(2)));
         const h2 h = {(_Float16)f0, (_Float16)f1};
         return __builtin_bit_cast(uint32_t, h);                       // q = 0 gives +0.0, code 0
@@ -98,6 +99,130 @@ __device__ __forceinline__ uint32_t encode_e3m2(int q, int b) {
     return (uint32_t)((0xCBA986420ull >> (4 * mag)) & 0xFull) | (v < 0 ? 32u : 0u);
 }
 
+constexpr int ACTIVE = 0x7FFF;
+
+// Element state shared by the two slicing kernels.  Dormant (not yet representable exactly with F fraction bits of
+// the current unit): tv = signed 53-bit significand, pk = (E + F) | (cd << 16) with x = tv * 2^E and
+// cd = ceil(log2 |x|).  Active: tv = T = x^(p) / 2^(c_p - b) * 2^F as a signed 64-bit integer (|x^(p)| <= 2^(c_p)
+// bounds |T| by 2^(b+F) = 2^60), pk = ACTIVE.  An element becomes active at the first slice whose unit 2^u satisfies
+// u <= E + F and stays so.
+__device__ __forceinline__ void decode_element(uint64_t w, int F, int64_t& tv, int& pk, int& cmax, bool& nonfinite) {
+    const int e11 = (int)((w >> 52) & 0x7FF);
+    uint64_t mm = w & 0x000FFFFFFFFFFFFFull;
+    nonfinite |= (e11 == 0x7FF);
+    int E = -1074;
+    if (e11 != 0) { mm |= 0x0010000000000000ull; E = e11 - 1075; }
+    const int L = 64 - __clzll((long long)mm);                       // bit length (0 for mm == 0)
+    const int cd = E + L - (((mm & (mm - 1)) == 0) ? 1 : 0);         // smallest c with |x| <= 2^c
+    tv = (w >> 63) ? -(int64_t)mm : (int64_t)mm;
+    pk = mm == 0 ? ACTIVE : (((E + F) & 0xFFFF) | (cd << 16));
+    cmax = (mm != 0 && cd > cmax) ? cd : cmax;
+}
+
+// Eq. 5-8 for one element and one slice whose unit is 2^unit: returns q, leaves the exact remainder in (T, st), and
+// keeps track of the largest remainder of the active elements (rmax, in units of 2^(unit - F)) and of the largest
+// ceil(log2 |x|) of the still dormant ones (cdorm).  rescale: left shift that brings an active remainder from the
+// previous slice's unit to this one.  WIDE: the format has slices of more than 7 bits (FP16 only).
+template <bool WIDE>
+__device__ __forceinline__ int slice_element(int64_t& T, int& st, int unit, int rescale, int F, int64_t round_bias, uint64_t& rmax,
+                                             int& cdorm) {
+    int q = 0;
+    bool active = st == ACTIVE;
+    if (active) {
+        T <<= rescale;
+    } else {
+        const int ef = (int)(short)(st & 0xFFFF);
+        if (unit <= ef) {                                  // representable now: x / 2^unit * 2^F
+            T <<= (ef - unit);
+            st = ACTIVE;
+            active = true;
+        } else if (WIDE && unit - ef + F <= 53) {
+            // Wide slices only (b >= 8, fewer than 53 fraction bits): the element reaches the unit but its
+            // low bits do not fit the fixed-point form yet.  Round its integer form tv * 2^E directly, by
+            // sh = unit - E bits, and let the remainder wait on as a dormant element with the same E.
+            const int sh = unit - ef + F;                  // F < sh <= 53
+            const int64_t q64 = (T + (((int64_t)1 << (sh - 1)) - 1) + ((T >> sh) & 1)) >> sh;
+            q = (int)q64;
+            T -= q64 << sh;
+            const uint64_t ar = (uint64_t)(T < 0 ? -T : T);
+            if (ar == 0) {
+                st = ACTIVE;                               // nothing left: an active zero
+            } else {
+                const int L = 64 - __clzll((long long)ar);
+                const int cd = ef - F + L - (((ar & (ar - 1)) == 0) ? 1 : 0);
+                st = (st & 0xFFFF) | (cd << 16);
+                cdorm = cd > cdorm ? cd : cdorm;
+            }
+        } else {
+            const int cd = st >> 16;
+            cdorm = cd > cdorm ? cd : cdorm;               // |x| < 2^(unit-1): q = 0, remainder = x
+        }
+    }
+    if (active) {
+        // nearest integer to T / 2^F, ties to even (two's complement form), and the exact remainder
+        const int64_t q64 = (T + round_bias + ((T >> F) & 1)) >> F;
+        q = (int)q64;
+        T -= q64 << F;
+        const uint64_t ar = (uint64_t)(T < 0 ? -T : T);
+        rmax = ar > rmax ? ar : rmax;
+    }
+    return q;
+}
+
+// Stores the Type2 codes of eight consecutive inner indices ke .. ke+7 of vector `row` into slice matrix dst_slice
+// (internal layout, see layout.hpp).
+template <int FMT>
+__device__ __forceinline__ void store_codes(const int (&qs)[8], int64_t ke, uint8_t* dst_slice, int64_t v_rows_pad, int64_t row, int b) {
+    constexpr bool FP16 = FMT == FMT_FP16;
+    constexpr bool FP6 = fmt_is_fp6(FMT);
+    constexpr int EPC = FP16 ? CHUNK_BYTES / 2 : CHUNK_BYTES;
+    constexpr int ROWB = FP6 ? CHUNK_BYTES_FP6 : CHUNK_BYTES;
+    if constexpr (FP6) {
+        // eight 6-bit codes = 48 bits: octet j of the 24-byte string of k-group g, i.e. bytes
+        // 6j .. 6j+5 of the string, whose first 16 bytes live in the 16-byte plane of g and the rest in the
+        // 8-byte plane (see layout.hpp).  Written as one 32-bit and one 16-bit store, both naturally aligned.
+        uint64_t w48 = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            w48 |= (uint64_t)(FMT == FMT_FP6_E3M2 ? encode_e3m2(qs[e], b) : encode_e2m3(qs[e], b)) << (6 * e);
+        const int64_t kc = ke / EPC;
+        const int o = (int)((ke % EPC) / 8), g = o >> 2, j = o & 3;
+        uint8_t* const chunk = dst_slice + (size_t)kc * v_rows_pad * ROWB;
+        uint8_t* const p16 = chunk + ((size_t)g * v_rows_pad + row) * 16;
+        uint8_t* const p8 = chunk + (size_t)v_rows_pad * 32 + ((size_t)g * v_rows_pad + row) * 8;
+        uint8_t* d32 = j == 0 ? p16 : j == 1 ? p16 + 8 : j == 2 ? p16 + 12 : p8 + 4;
+        uint8_t* d16 = j == 0 ? p16 + 4 : j == 1 ? p16 + 6 : j == 2 ? p8 : p8 + 2;
+        const bool low32 = (j & 1) == 0;                   // bytes 6j.. start 4-byte aligned for even j
+        *reinterpret_cast<uint32_t*>(d32) = low32 ? (uint32_t)w48 : (uint32_t)(w48 >> 16);
+        *reinterpret_cast<uint16_t*>(d16) = low32 ? (uint16_t)(w48 >> 32) : (uint16_t)w48;
+    } else {
+        uint32_t c2[4];                                            // two codes each
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c2[e] = encode_type2_pair<FMT>(qs[2 * e], qs[2 * e + 1], b);
+        const int64_t kc = ke / EPC;
+        uint8_t* dst = dst_slice + ((size_t)kc * v_rows_pad + row) * CHUNK_BYTES + (ke % EPC) * (FP16 ? 2 : 1);
+        if (FP16) {
+            uint4 w;
+            w.x = c2[0];
+            w.y = c2[1];
+            w.z = c2[2];
+            w.w = c2[3];
+            *reinterpret_cast<uint4*>(dst) = w;
+        } else {
+            uint2 w;
+            w.x = c2[0] | (c2[1] << 16);
+            w.y = c2[2] | (c2[3] << 16);
+            *reinterpret_cast<uint2*>(dst) = w;
+        }
+    }
+}
+
+// smallest c with v * 2^(unit - F) <= 2^c, for v != 0
+__device__ __forceinline__ int ceil_log2_scaled(uint64_t v, int unit, int F) {
+    const int L = 64 - __clzll((long long)v);
+    return unit - F + L - (((v & (v - 1)) == 0) ? 1 : 0);
+}
+
 template <int U, int TPR, int FMT>
 __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArgs a) {
     constexpr bool FP16 = FMT == FMT_FP16;
@@ -107,7 +232,6 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
     constexpr int EPC = FP16 ? CHUNK_BYTES / 2 : CHUNK_BYTES;   // elements per chunk
     constexpr int ROWB = FP6 ? CHUNK_BYTES_FP6 : CHUNK_BYTES;   // bytes per vector and chunk
     constexpr int WAVES_PER_ROW = TPR / 64;
-    constexpr int ACTIVE = 0x7FFF;
     __shared__ int red[2][BLOCK / 64];
 
     const int tr = threadIdx.x % TPR;
@@ -136,9 +260,7 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
     // signed 64-bit integer.  |x^(p)| <= 2^(c_p) bounds |T| by 2^(b+F) = 2^60.
     const int F = 60 - a.b;
 
-    // Element state.  Dormant (not yet representable exactly with F fraction bits of the current unit): tv = signed
-    // 53-bit significand, pk = (E + F) | (cd << 16) with x = tv * 2^E and cd = ceil(log2 |x|).  Active: tv = T,
-    // pk = ACTIVE.  An element becomes active at the first slice whose unit 2^u satisfies u <= E + F and stays so.
+    // element state (see decode_element)
     int64_t tv[8 * U];
     int pk[8 * U];
     bool nonfinite = false;
@@ -161,19 +283,7 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
             for (int e = 0; e < 8; ++e) bits[e] = (ke + e < klen) ? __double_as_longlong(src[ke + e]) : 0ull;
         }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const uint64_t w = bits[e];
-            const int e11 = (int)((w >> 52) & 0x7FF);
-            uint64_t mm = w & 0x000FFFFFFFFFFFFFull;
-            nonfinite |= (e11 == 0x7FF);
-            int E = -1074;
-            if (e11 != 0) { mm |= 0x0010000000000000ull; E = e11 - 1075; }
-            const int L = 64 - __clzll((long long)mm);                       // bit length (0 for mm == 0)
-            const int cd = E + L - (((mm & (mm - 1)) == 0) ? 1 : 0);         // smallest c with |x| <= 2^c
-            tv[8 * u + e] = (w >> 63) ? -(int64_t)mm : (int64_t)mm;
-            pk[8 * u + e] = mm == 0 ? ACTIVE : (((E + F) & 0xFFFF) | (cd << 16));
-            cmax = (mm != 0 && cd > cmax) ? cd : cmax;
-        }
+        for (int e = 0; e < 8; ++e) decode_element(bits[e], F, tv[8 * u + e], pk[8 * u + e], cmax, nonfinite);
     }
     if (nonfinite) atomicOr(a.flags, 1);
 
@@ -219,106 +329,124 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
         for (int u = 0; u < U; ++u) {
             int qs[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int i = 8 * u + e;
-                int64_t T = tv[i];
-                const int st = pk[i];
-                int q = 0;
-                bool active = st == ACTIVE;
-                if (active) {
-                    T <<= rescale;
-                } else {
-                    const int ef = (int)(short)(st & 0xFFFF);
-                    if (unit <= ef) {                                  // representable now: x / 2^unit * 2^F
-                        T <<= (ef - unit);
-                        pk[i] = ACTIVE;
-                        active = true;
-                    } else if (FP16 && unit - ef + F <= 53) {       // only FP16 has slices of more than 7 bits
-                        // Wide slices only (b >= 8, fewer than 53 fraction bits): the element reaches the unit but its
-                        // low bits do not fit the fixed-point form yet.  Round its integer form tv * 2^E directly, by
-                        // sh = unit - E bits, and let the remainder wait on as a dormant element with the same E.
-                        const int sh = unit - ef + F;                  // F < sh <= 53
-                        const int64_t q64 = (T + (((int64_t)1 << (sh - 1)) - 1) + ((T >> sh) & 1)) >> sh;
-                        q = (int)q64;
-                        T -= q64 << sh;
-                        tv[i] = T;
-                        const uint64_t ar = (uint64_t)(T < 0 ? -T : T);
-                        if (ar == 0) {
-                            pk[i] = ACTIVE;                            // nothing left: an active zero
-                        } else {
-                            const int L = 64 - __clzll((long long)ar);
-                            const int cd = ef - F + L - (((ar & (ar - 1)) == 0) ? 1 : 0);
-                            pk[i] = (st & 0xFFFF) | (cd << 16);
-                            cdorm = cd > cdorm ? cd : cdorm;
-                        }
-                    } else {
-                        const int cd = st >> 16;
-                        cdorm = cd > cdorm ? cd : cdorm;               // |x| < 2^(unit-1): q = 0, remainder = x
-                    }
-                }
-                if (active) {
-                    // nearest integer to T / 2^F, ties to even (two's complement form), and the exact remainder
-                    const int64_t q64 = (T + round_bias + ((T >> F) & 1)) >> F;
-                    q = (int)q64;
-                    T -= q64 << F;
-                    const uint64_t ar = (uint64_t)(T < 0 ? -T : T);
-                    rmax = ar > rmax ? ar : rmax;
-                    tv[i] = T;
-                }
-                qs[e] = q;
-            }
+            for (int e = 0; e < 8; ++e) qs[e] = slice_element<FP16>(tv[8 * u + e], pk[8 * u + e], unit, rescale, F, round_bias, rmax, cdorm);
             const int64_t ke = 8 * ((int64_t)tr + (int64_t)TPR * u);
-            if constexpr (FP6) {
-                // eight 6-bit codes = 48 bits: octet j of the 24-byte string of k-group g, i.e. bytes
-                // 6j .. 6j+5 of the string, whose first 16 bytes live in the 16-byte plane of g and the rest in the
-                // 8-byte plane (see layout.hpp).  Written as one 32-bit and one 16-bit store, both naturally aligned.
-                uint64_t w48 = 0;
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    w48 |= (uint64_t)(FMT == FMT_FP6_E3M2 ? encode_e3m2(qs[e], a.b) : encode_e2m3(qs[e], a.b)) << (6 * e);
-                if (ke < padded && v_slices != nullptr) {
-                    const int64_t kc = ke / EPC;
-                    const int o = (int)((ke % EPC) / 8), g = o >> 2, j = o & 3;
-                    uint8_t* const chunk = dst_slice + (size_t)kc * v_rows_pad * ROWB;
-                    uint8_t* const p16 = chunk + ((size_t)g * v_rows_pad + row) * 16;
-                    uint8_t* const p8 = chunk + (size_t)v_rows_pad * 32 + ((size_t)g * v_rows_pad + row) * 8;
-                    uint8_t* d32 = j == 0 ? p16 : j == 1 ? p16 + 8 : j == 2 ? p16 + 12 : p8 + 4;
-                    uint8_t* d16 = j == 0 ? p16 + 4 : j == 1 ? p16 + 6 : j == 2 ? p8 : p8 + 2;
-                    const bool low32 = (j & 1) == 0;                   // bytes 6j.. start 4-byte aligned for even j
-                    *reinterpret_cast<uint32_t*>(d32) = low32 ? (uint32_t)w48 : (uint32_t)(w48 >> 16);
-                    *reinterpret_cast<uint16_t*>(d16) = low32 ? (uint16_t)(w48 >> 32) : (uint16_t)w48;
-                }
-            } else {
-                uint32_t c2[4];                                            // two codes each
-#pragma unroll
-                for (int e = 0; e < 4; ++e) c2[e] = encode_type2_pair<FP16>(qs[2 * e], qs[2 * e + 1], a.b);
-                if (ke < padded && v_slices != nullptr) {
-                    const int64_t kc = ke / EPC;
-                    uint8_t* dst = dst_slice + ((size_t)kc * v_rows_pad + row) * CHUNK_BYTES + (ke % EPC) * (FP16 ? 2 : 1);
-                    if (FP16) {
-                        uint4 w;
-                        w.x = c2[0];
-                        w.y = c2[1];
-                        w.z = c2[2];
-                        w.w = c2[3];
-                        *reinterpret_cast<uint4*>(dst) = w;
-                    } else {
-                        uint2 w;
-                        w.x = c2[0] | (c2[1] << 16);
-                        w.y = c2[2] | (c2[3] << 16);
-                        *reinterpret_cast<uint2*>(dst) = w;
-                    }
-                }
-            }
+            if (ke < padded && v_slices != nullptr) store_codes<FMT>(qs, ke, dst_slice, v_rows_pad, row, a.b);
         }
         if (tr == 0 && v_slices != nullptr) v_exps[(t * a.s + p) * v_rows_pad + row] = c;
         // this thread's candidate for the next exponent: remainders are rmax * 2^(unit - F)
         cmax = cdorm;
         if (rmax != 0) {
-            const int L = 64 - __clzll((long long)rmax);
-            const int ca = unit - F + L - (((rmax & (rmax - 1)) == 0) ? 1 : 0);
+            const int ca = ceil_log2_scaled(rmax, unit, F);
             cmax = ca > cmax ? ca : cmax;
         }
+    }
+}
+
+// The same slicing for blocks too long for the registers of one workgroup: one workgroup of 1024 threads per vector
+// and block streams through the vector once per slice, with the element state (decode_element) kept in work memory
+// between the slices: tv_state / pk_state hold one int64 / int32 per element of the (real) vectors.
+template <int FMT>
+__global__ void __launch_bounds__(1024) split_stream_kernel(SplitArgs a, int64_t* tv_state, int* pk_state) {
+    constexpr bool FP16 = FMT == FMT_FP16;
+    constexpr int EPC = FP16 ? CHUNK_BYTES / 2 : CHUNK_BYTES;
+    constexpr int ROWB = fmt_is_fp6(FMT) ? CHUNK_BYTES_FP6 : CHUNK_BYTES;
+    __shared__ int red[2][16];
+    const int tid = threadIdx.x, wave = tid >> 6;
+    const bool second = blockIdx.x >= a.wg_first;
+    const SplitVectors& v = second ? a.v[1] : a.v[0];
+    const int64_t row = blockIdx.x - (second ? a.wg_first : 0u);
+    const int64_t t = blockIdx.y, T = gridDim.y;
+    const int64_t k0 = t * a.kb;
+    int64_t klen = a.k - k0;
+    if (klen > a.kb) klen = a.kb;
+    const int64_t padded = a.chunks * EPC, n_oct = padded / 8;
+    const int F = 60 - a.b;
+    if (row >= v.rows) {
+        // a padding vector: zero codes and c = 0 in every slice
+        if (v.slices == nullptr) return;
+        const int zero8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int p = 0; p < a.s; ++p) {
+            uint8_t* const dst_slice = v.slices + (size_t)((t * a.s + p) * a.chunks) * (size_t)v.rows_pad * ROWB;
+            for (int64_t o = tid; o < n_oct; o += 1024) store_codes<FMT>(zero8, 8 * o, dst_slice, v.rows_pad, row, a.b);
+            if (tid == 0) v.exps[(t * a.s + p) * v.rows_pad + row] = 0;
+        }
+        return;
+    }
+    // this vector's state: real vectors of the first operand, then those of the second, each with T blocks
+    const int64_t vec = (second ? a.v[0].rows : 0) + row;
+    int64_t* const tv = tv_state + (size_t)(vec * T + t) * padded;
+    int* const pk = pk_state + (size_t)(vec * T + t) * padded;
+
+    // block-wide maximum of an int, double-buffered so that one barrier per reduction suffices
+    int round = 0;
+    auto block_max = [&](int val) -> int {
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_xor(val, off, 64);
+            val = o > val ? o : val;
+        }
+        if ((tid & 63) == 0) red[round & 1][wave] = val;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int o = red[round & 1][w];
+            val = o > val ? o : val;
+        }
+        ++round;
+        return val;
+    };
+
+    bool nonfinite = false;
+    int cmax = NO_ELEM;
+    const double* src = v.X + row * v.ldv + k0;
+    for (int64_t o = tid; o < n_oct; o += 1024) {
+        const int64_t ke = 8 * o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint64_t w = (ke + e < klen) ? (uint64_t)__double_as_longlong(src[ke + e]) : 0ull;
+            int64_t T0;
+            int st;
+            decode_element(w, F, T0, st, cmax, nonfinite);
+            tv[ke + e] = T0;
+            pk[ke + e] = st;
+        }
+    }
+    if (nonfinite) atomicOr(a.flags, 1);
+    cmax = block_max(cmax);
+
+    int c_prev = 0;
+    for (int p = 0; p < a.s; ++p) {
+        if (v.slices == nullptr && cmax != NO_ELEM && tid == 0) atomicMax(a.flags + 1, p + 1);     // count-only mode
+        const int c = (cmax == NO_ELEM) ? 0 : cmax;
+        const int unit = c - a.b;
+        int rescale = p == 0 ? 0 : c_prev - c;
+        rescale = rescale < 0 ? 0 : (rescale > 63 ? 63 : rescale);
+        c_prev = c;
+        uint8_t* const dst_slice = v.slices + (size_t)((t * a.s + p) * a.chunks) * (size_t)v.rows_pad * ROWB;
+        uint64_t rmax = 0;
+        int cdorm = NO_ELEM;
+        const int64_t round_bias = ((int64_t)1 << (F - 1)) - 1;
+        for (int64_t o = tid; o < n_oct; o += 1024) {
+            const int64_t ke = 8 * o;
+            int qs[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                int64_t T0 = tv[ke + e];
+                int st = pk[ke + e];
+                qs[e] = slice_element<FP16>(T0, st, unit, rescale, F, round_bias, rmax, cdorm);
+                tv[ke + e] = T0;
+                pk[ke + e] = st;
+            }
+            if (v.slices != nullptr) store_codes<FMT>(qs, ke, dst_slice, v.rows_pad, row, a.b);
+        }
+        if (tid == 0 && v.slices != nullptr) v.exps[(t * a.s + p) * v.rows_pad + row] = c;
+        cmax = cdorm;
+        if (rmax != 0) {
+            const int ca = ceil_log2_scaled(rmax, unit, F);
+            cmax = ca > cmax ? ca : cmax;
+        }
+        cmax = block_max(cmax);
     }
 }
 
@@ -356,31 +484,34 @@ __global__ void __launch_bounds__(256) export_slices_kernel(const uint8_t* __res
     }
 }
 
-// One workgroup per 256-vector tile and block: for every slice p, is c_p - c_(p+1) the same for all real vectors?
-// The first tiles_first workgroups of a grid row belong to the first operand, the rest to the second.
+// One workgroup per 256 vectors and block, one half-wave per group of 32 vectors: for every slice p, is c_p - c_(p+1)
+// the same for all real vectors of the group?  The first tiles_first workgroups of a grid row belong to the first
+// operand, the rest to the second.
 struct DeltaOperand {
     const int32_t* exps;
     int32_t* deltas;
     int64_t rows, rows_pad;
 };
 __global__ void __launch_bounds__(256) delta_kernel(DeltaOperand o0, DeltaOperand o1, unsigned tiles_first, int s) {
-    __shared__ int ref;
     const bool second = blockIdx.x >= tiles_first;
     const int32_t* const exps = second ? o1.exps : o0.exps;
     int32_t* const deltas = second ? o1.deltas : o0.deltas;
     const int64_t rows = second ? o1.rows : o0.rows, rows_pad = second ? o1.rows_pad : o0.rows_pad;
-    const int64_t tile = blockIdx.x - (second ? tiles_first : 0u), tiles = rows_pad / TILE, t = blockIdx.y;
+    const int64_t tile = blockIdx.x - (second ? tiles_first : 0u), groups = rows_pad / LINK_ROWS, t = blockIdx.y;
     const int64_t row = tile * TILE + threadIdx.x;
+    const int64_t group = row / LINK_ROWS;
+    const int lane = threadIdx.x & 63, half = lane & 32;
     const int32_t* e = exps + (size_t)t * s * rows_pad;
-    int32_t* out = deltas + ((size_t)t * tiles + tile) * s;
+    int32_t* out = deltas + ((size_t)t * groups + group) * s;
     for (int p = 0; p + 1 < s; ++p) {
         const int d = e[(size_t)p * rows_pad + row] - e[(size_t)(p + 1) * rows_pad + row];
-        if (threadIdx.x == 0) ref = d;               // the first vector of a tile is always a real one
-        __syncthreads();
-        const int same = __syncthreads_and(row >= rows || d == ref);
-        if (threadIdx.x == 0) out[p] = same ? ref : DELTA_IRREGULAR;
+        // the first vector of a group is a real one, or the whole group is padding (then every d is 0)
+        const int ref = __shfl(d, half, 64);
+        const unsigned long long ok = __ballot(row >= rows || d == ref);
+        const bool same = (uint32_t)(ok >> half) == 0xFFFFFFFFu;
+        if ((lane & 31) == 0) out[p] = same ? ref : DELTA_IRREGULAR;
     }
-    if (threadIdx.x == 0) out[s - 1] = DELTA_IRREGULAR;
+    if ((lane & 31) == 0) out[s - 1] = DELTA_IRREGULAR;
 }
 
 template <int U, int TPR>
@@ -393,7 +524,25 @@ hipError_t launch_split_cfg(const SplitArgs& a_in, int fmt, int64_t T, hipStream
     if (fmt == FMT_FP16) hipLaunchKernelGGL((split_kernel<U, TPR, FMT_FP16>), grid, dim3(BLOCK), 0, st, a);
     else if (fmt == FMT_FP6) hipLaunchKernelGGL((split_kernel<U, TPR, FMT_FP6>), grid, dim3(BLOCK), 0, st, a);
     else if (fmt == FMT_FP6_E3M2) hipLaunchKernelGGL((split_kernel<U, TPR, FMT_FP6_E3M2>), grid, dim3(BLOCK), 0, st, a);
+    else if (fmt == FMT_INT8) hipLaunchKernelGGL((split_kernel<U, TPR, FMT_INT8>), grid, dim3(BLOCK), 0, st, a);
     else hipLaunchKernelGGL((split_kernel<U, TPR, FMT_FP8>), grid, dim3(BLOCK), 0, st, a);
+    return hipGetLastError();
+}
+
+// blocks too long for the register-resident kernel: one workgroup per vector (real and padding) and block
+hipError_t launch_split_stream(const SplitArgs& a_in, int fmt, int64_t T, void* state, hipStream_t st) {
+    if (state == nullptr) return hipErrorInvalidValue;
+    SplitArgs a = a_in;
+    a.wg_first = (unsigned)a.v[0].rows_pad;
+    const int64_t elems = (a.v[0].rows + a.v[1].rows) * T * a.chunks * (fmt == FMT_FP16 ? CHUNK_BYTES / 2 : CHUNK_BYTES);
+    int64_t* tv = static_cast<int64_t*>(state);
+    int* pk = reinterpret_cast<int*>(tv + elems);
+    dim3 grid(a.wg_first + (unsigned)a.v[1].rows_pad, (unsigned)T);
+    if (fmt == FMT_FP16) hipLaunchKernelGGL((split_stream_kernel<FMT_FP16>), grid, dim3(1024), 0, st, a, tv, pk);
+    else if (fmt == FMT_FP6) hipLaunchKernelGGL((split_stream_kernel<FMT_FP6>), grid, dim3(1024), 0, st, a, tv, pk);
+    else if (fmt == FMT_FP6_E3M2) hipLaunchKernelGGL((split_stream_kernel<FMT_FP6_E3M2>), grid, dim3(1024), 0, st, a, tv, pk);
+    else if (fmt == FMT_INT8) hipLaunchKernelGGL((split_stream_kernel<FMT_INT8>), grid, dim3(1024), 0, st, a, tv, pk);
+    else hipLaunchKernelGGL((split_stream_kernel<FMT_FP8>), grid, dim3(1024), 0, st, a, tv, pk);
     return hipGetLastError();
 }
 
@@ -417,8 +566,13 @@ SplitVectors split_vectors(const double* X, int64_t ldv, const Plan& pl, const O
 }
 }  // namespace
 
+size_t split_state_bytes(const Plan& pl, int64_t rows_a, int64_t rows_b) {
+    if (pl.kb <= MAX_K_BLOCK_IN_REGISTERS) return 0;
+    return (size_t)(rows_a + rows_b) * pl.T * pl.chunks * pl.epc * (sizeof(int64_t) + sizeof(int));
+}
+
 hipError_t launch_split(const double* X0, int64_t ldv0, const Operand* op0, const double* X1, int64_t ldv1, const Operand* op1,
-                        const Plan& pl, int* flags, hipStream_t st) {
+                        const Plan& pl, int* flags, void* long_state, hipStream_t st) {
     SplitArgs a;
     a.v[0] = split_vectors(X0, ldv0, pl, op0);
     a.v[1] = split_vectors(X1, ldv1, pl, op1);
@@ -427,6 +581,7 @@ hipError_t launch_split(const double* X0, int64_t ldv0, const Operand* op0, cons
     if (a.v[0].rows_pad + a.v[1].rows_pad == 0 || pl.T == 0) return hipSuccess;
     const int64_t vectors = (a.v[0].rows_pad + a.v[1].rows_pad) * pl.T;
     const int fmt = pl.fmt;
+    if (pl.kb > MAX_K_BLOCK_IN_REGISTERS) return launch_split_stream(a, fmt, pl.T, long_state, st);
     const int64_t octets = pl.chunks * pl.epc / 8;                              // per vector and block, padded
     // sixteen elements per thread (U = 2) is the measured optimum: more elements per thread cost registers and with
     // them the occupancy that hides the latency of the dependent integer chains (64 per thread: one wave per SIMD)
@@ -442,18 +597,19 @@ hipError_t launch_split(const double* X0, int64_t ldv0, const Operand* op0, cons
     if (octets <= 512) return launch_split_cfg<2, 256>(a, fmt, pl.T, st);
     if (octets <= 1024) return launch_split_cfg<2, 512>(a, fmt, pl.T, st);
     if (octets <= 2048) return launch_split_cfg<2, 1024>(a, fmt, pl.T, st);
-    if (octets <= 4096) return launch_split_cfg<4, 1024>(a, fmt, pl.T, st);
-    return hipErrorInvalidValue;                                                // the planner rejects longer blocks
+    // 32 elements per thread would cover blocks of up to 32768 elements, but at the 128 registers a thread of a
+    // 1024-thread workgroup has, that variant lives on more than a hundred spilled registers; such blocks are streamed
+    return hipErrorInvalidValue;
 }
 
-hipError_t launch_count_slices(const double* X, int64_t ldv, const Plan& pl, int64_t rows, int* flags, hipStream_t st) {
+hipError_t launch_count_slices(const double* X, int64_t ldv, const Plan& pl, int64_t rows, int* flags, void* long_state, hipStream_t st) {
     Plan cp = pl;
     cp.s = MAX_SLICES + 1;                       // one more than the library can use: "not exhausted" is reported as 33
     Operand op;
     op.rows = rows;
     op.rows_pad = (rows + TILE - 1) / TILE * TILE;
     op.slices = nullptr; op.exps = nullptr; op.deltas = nullptr;
-    return launch_split(X, ldv, &op, nullptr, 0, nullptr, cp, flags, st);
+    return launch_split(X, ldv, &op, nullptr, 0, nullptr, cp, flags, long_state, st);
 }
 
 hipError_t launch_deltas(const Plan& pl, const Operand* op0, const Operand* op1, hipStream_t st) {
@@ -463,7 +619,7 @@ hipError_t launch_deltas(const Plan& pl, const Operand* op0, const Operand* op1,
     for (int i = 0; i < 2; ++i)
         if (ops[i] != nullptr && ops[i]->rows > 0) o[i] = DeltaOperand{ops[i]->exps, ops[i]->deltas, ops[i]->rows, ops[i]->rows_pad};
     const unsigned t0 = (unsigned)(o[0].rows_pad / TILE), t1 = (unsigned)(o[1].rows_pad / TILE);
-    if (t0 + t1 == 0 || pl.T == 0) return hipSuccess;
+    if (t0 + t1 == 0 || pl.T == 0 || pl.s == 0) return hipSuccess;
     hipLaunchKernelGGL(delta_kernel, dim3(t0 + t1, (unsigned)pl.T), dim3(256), 0, st, o[0], o[1], t0, pl.s);
     return hipGetLastError();
 }

@@ -30,11 +30,12 @@ class Workspace:
         binding.ozaki_set_workspace(self.buf, self.buf.numel())
 
     @classmethod
-    def for_problem(cls, m, n, k, slice_format, num_slices, k_block, minimum: bool = False, scaled: bool = False) -> "Workspace":
-        fn = binding.ozaki_workspace_min_bytes if minimum else binding.ozaki_workspace_bytes
+    def for_problem(cls, m, n, k, slice_format, num_slices, k_block, minimum: bool = False, scaled: bool = False,
+                    pair_set: int = binding.PAIRS_TRIANGLE) -> "Workspace":
         if scaled:
-            fn = binding.ozaki_workspace_bytes_scaled
-        nbytes = fn(m, n, k, slice_format, num_slices, k_block)
+            nbytes = binding.ozaki_workspace_bytes_scaled(m, n, k, slice_format, num_slices, k_block)
+        else:
+            nbytes = binding.ozaki_workspace_bytes_ex(m, n, k, slice_format, num_slices, k_block, pair_set, minimum)
         if nbytes == 0 and m and n and k:
             raise ValueError("infeasible or invalid problem")
         return cls(nbytes)

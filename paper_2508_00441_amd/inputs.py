@@ -46,6 +46,27 @@ def full_mantissa_one_binade(rows: int, cols: int, rng: np.random.Generator) -> 
     return bits.view(np.float64)
 
 
+def nasty_rows(rng: np.random.Generator, rows: int, k: int) -> np.ndarray:
+    """rows x k matrix (rows >= 9) whose first nine rows are the corner cases of the slicing step: a zero vector, a
+    maximum that is a power of two, one just above a power of two, a row that needs a single slice, a half-empty row, a
+    row with one entry 2^300 times the rest, a full-significand one-binade row with random signs, a row scaled down by
+    2^-400, and a row of exact ties of the first slice's rounding; the other rows are phi = 3 entries."""
+    X = phi_matrix(rows, k, 3.0, rng)
+    X[0, :] = 0.0                                     # zero vector: c := 0
+    X[1, :] = 1.0                                     # max is a power of two
+    X[2, :] = np.nextafter(1.0, 2.0)                  # just above a power of two
+    X[3, :] = np.ldexp(rng.integers(-16, 17, k).astype(np.float64), -3)   # one-slice row
+    X[4, : k // 2] = 0.0
+    X[5, 0] = 2.0 ** 300
+    X[6, :] = full_mantissa_one_binade(1, k, rng)[0] * np.where(rng.random(k) < 0.5, -1, 1)
+    X[7, :] *= 2.0 ** -400
+    # ties: entries exactly half way between two slice values of the first slice
+    X[8, :] = 0.0
+    X[8, 0] = 1.0
+    X[8, 1:9] = (2 * np.arange(8) + 1) / 32.0         # odd multiples of 2^-5 when the first ulp is 2^-4
+    return X
+
+
 #: The benchmark configurations: name -> shape, phi, slice format, k_block (0 = no blocking), accumulation mode.
 CONFIGS = {
     "c1_256_fp8_hw":        dict(m=256,   n=256,   k=256,   phi=0.5, fmt="fp8",  k_block=0,    accum="hw"),

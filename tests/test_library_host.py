@@ -39,12 +39,18 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_planner_matches_eq_1_to_3():
-    for fmt, fid in (("fp8", lib.SLICE_FP8_E4M3), ("fp16", lib.SLICE_FP16), ("fp6", lib.SLICE_FP6_E2M3), ("fp6_e3m2", lib.SLICE_FP6_E3M2)):
-        for k in [1, 2, 3, 8, 16, 17, 64, 65, 255, 256, 1024, 1025, 4096, 5000, 16384, 16385, 65536, 65537, 262144, 1 << 24]:
+    for fmt, fid in (("fp8", lib.SLICE_FP8_E4M3), ("fp16", lib.SLICE_FP16), ("fp6", lib.SLICE_FP6_E2M3), ("fp6_e3m2", lib.SLICE_FP6_E3M2),
+                     ("int8", lib.SLICE_INT8)):
+        for k in [1, 2, 3, 8, 16, 17, 64, 65, 255, 256, 1024, 1025, 4096, 5000, 16384, 16385, 65536, 65537, 262144, 524287, 524288,
+                  1 << 24]:
             p = oz.make_plan(k, fmt)
             assert lib.ozaki_plan(k, fid) == (p.rho, p.b), (fmt, k)
     with pytest.raises(lib.OzakiError) as e:
         lib.ozaki_plan((1 << 24) + 1, lib.SLICE_FP8_E4M3)
+    assert e.value.status == lib.STATUS_INFEASIBLE
+    assert lib.ozaki_plan((1 << 31) - 1, lib.SLICE_INT8) == (53, 0)
+    with pytest.raises(lib.OzakiError) as e:
+        lib.ozaki_plan(1 << 31, lib.SLICE_INT8)
     assert e.value.status == lib.STATUS_INFEASIBLE
     with pytest.raises(lib.OzakiError) as e:
         lib.ozaki_plan(0, 0)
@@ -56,11 +62,12 @@ def test_planner_matches_eq_1_to_3():
 
 def test_k_block_suggestion_keeps_the_plan_feasible():
     """A heuristic (parity unpinned); what is checked: the suggested block is accepted by the planner."""
-    for fid in (lib.SLICE_FP8_E4M3, lib.SLICE_FP16, lib.SLICE_FP6_E2M3, lib.SLICE_FP6_E3M2):
-        for k in (1, 100, 4096, 4097, 16384, 32768, 32769, 1 << 20):
+    for fid in (lib.SLICE_FP8_E4M3, lib.SLICE_FP16, lib.SLICE_FP6_E2M3, lib.SLICE_FP6_E3M2, lib.SLICE_INT8):
+        for k in (1, 100, 4096, 4097, 16384, 32768, 32769, 65536, 65537, 1 << 20, 1 << 26):
             kb = lib.ozaki_suggest_k_block(k, fid)
-            assert 0 <= kb <= lib.MAX_K_BLOCK and (kb or k) <= lib.MAX_K_BLOCK
+            assert 0 <= kb <= k
             assert lib.ozaki_workspace_bytes(64, 64, k, fid, 4, kb) > 0
+            assert lib.ozaki_plan(kb or k, fid)[1] >= 3                        # the suggestion keeps the slices wide
     assert lib.ozaki_suggest_k_block(16384, lib.SLICE_FP16) == 4096 and lib.ozaki_suggest_k_block(16384, lib.SLICE_FP8_E4M3) == 0
     with pytest.raises(lib.OzakiError):
         lib.ozaki_suggest_k_block(16, 9)
@@ -73,16 +80,22 @@ def test_workspace_sizes():
     slices = 2 * 16 * 8192 * 8192
     assert full >= 136 * pair + slices + 8192 * 8192 * 8
     assert slices + 8192 * 8192 * 8 + pair < mini < full
-    # more pairs than the resident-product budget: capped, with room for the running FP64 sum
+    # more pairs than the resident-product budget: capped, with room for the running block sum (three 64-bit words)
     big = lib.ozaki_workspace_bytes(32768, 32768, 16384, 0, 13, 0)          # 91 products of 4 GiB
-    assert big < (160 << 30) + 2 * 13 * 32768 * 16384 + 3 * 32768 * 32768 * 8 + (1 << 20)
+    assert big < (160 << 30) + 2 * 13 * 32768 * 16384 + 32768 * 16384 * 8 + 3 * 32768 * 32768 * 8 + (16 << 20)   # + A transposed + three sum words
     assert lib.ozaki_workspace_bytes(16, 16, 16, 5, 4, 0) == 0          # bad format
-    assert lib.ozaki_workspace_bytes(16, 16, 1 << 20, 0, 4, 0) == 0     # block longer than the library supports
-    assert lib.ozaki_workspace_bytes(16, 16, 1 << 20, 0, 4, 8192) > 0
+    assert lib.ozaki_workspace_bytes(16, 16, 1 << 25, 0, 4, 0) == 0     # no slice width is exact for a block this long
+    assert lib.ozaki_workspace_bytes(16, 16, 1 << 25, 0, 4, 8192) > 0
+    # blocks beyond the register-resident slicing kernel need its streaming state: 12 bytes per (padded) element
+    long_ws = lib.ozaki_workspace_bytes(16, 16, 1 << 20, 0, 4, 0)
+    assert long_ws > lib.ozaki_workspace_bytes(16, 16, 1 << 20, 0, 4, 16384) + 12 * 32 * (1 << 20) - (1 << 20)
+    assert lib.ozaki_workspace_bytes(16, 16, 16, 0, 33, 0) == 0         # more slices than the library takes
     assert lib.ozaki_workspace_bytes(0, 0, 0, 0, 4, 0) >= 256
     tri = lib.ozaki_workspace_bytes(1024, 1024, 1024, 0, 8, 0)
-    allp = lib.ozaki_workspace_bytes(1024, 1024, 1024, 0, 8 | lib.PAIRS_ALL, 0)
+    allp = lib.ozaki_workspace_bytes_ex(1024, 1024, 1024, 0, 8, 0, lib.PAIRS_ALL, 0)
     assert allp - tri == (64 - 36) * 1024 * 1024 * 4                   # s*s instead of s(s+1)/2 products
+    assert lib.ozaki_workspace_bytes_ex(1024, 1024, 1024, 0, 8, 0, lib.PAIRS_TRIANGLE, 1) == lib.ozaki_workspace_min_bytes(1024, 1024, 1024, 0, 8, 0)
+    assert lib.ozaki_workspace_bytes_ex(1024, 1024, 1024, 0, 8, 0, 2, 0) == 0
 
 
 def test_argument_errors_are_reported_before_anything_is_launched():
@@ -94,9 +107,20 @@ def test_argument_errors_are_reported_before_anything_is_launched():
     assert f(1, 1, 1, None, 1, None, 1, None, 1, 0, -4, 0, 0) == -11
     assert f(1, 1, 1, None, 1, None, 1, None, 1, 0, 4, -1, 0) == -12
     assert f(1, 1, 1, None, 1, None, 1, None, 1, 0, 4, 0, 5) == -13
+    assert f(1, 1, 1, None, 1, None, 1, None, 1, 0, 4, 0, -1) == -13
     assert f(1, 1, 1, None, 1, None, 1, None, 1, 0, 4, 0, 0) == -8       # C missing
     assert f(1, 1, 1, None, 1, None, 1, 1 << 20, 1, 0, 4, 0, 0) == -4    # A missing
-    assert f(1, 1, 70000, None, 1, None, 1, None, 1, 0, 4, 0, 0) == lib.STATUS_INFEASIBLE
+    assert f(1, 1, 1 << 25, None, 1, None, 1, None, 1, 0, 4, 0, 0) == lib.STATUS_INFEASIBLE
+    assert f(1, 1, 1 << 25, None, 1, None, 1, None, 1, 0, 4, 4096, 0) == -8             # blocked: feasible, C missing
+    assert f(1, 1, 1, None, 1, None, 1, None, 1, 0, 33, 0, 0) == lib.STATUS_SLICE_COUNT
+    assert len({lib.status_string(c) for c in (1, 3, 4, 5, 6, 7)}) == 6                  # every cause has a message of its own
+    fx = lib.load().ozaki_dgemm_ex
+    assert fx(1, 1, 1, None, 1, None, 1, None, 1, 0, 4, 0, 0, 5, 0, 0) == -14
+    assert fx(1, 1, 1, None, 1, None, 1, None, 1, 0, 4, 0, 0, 1, 7, 0) == -15
+    assert fx(1, 1, 1, None, 1, None, 1, None, 1, 0, 4, 0, 2, 1, 1, 0) == -8             # exact mode, all pairs: C missing
+    fs = lib.load().ozaki_dgemm_static
+    assert fs(-1, 1, 1, None, 1, None, 1, None, 1, 0, 4, 0, 0) == -1
+    assert fs(4096, 4096, 4096, 1 << 20, 4096, 1 << 20, 4096, 1 << 20, 4096, 0, 13, 0, 0) == lib.STATUS_STATIC_LIMIT
     assert f(0, 0, 5, None, 1, None, 1, None, 1, 0, 4, 0, 0) == 0        # empty product: nothing to do
     assert "workspace" in lib.status_string(lib.STATUS_WORKSPACE)
     assert "argument" in lib.status_string(-3)
@@ -212,7 +236,8 @@ def test_product_rounded_sum_on_host_equals_chain_of_fpu_additions(host_emu):
     (terms about 2^b apart, least significant first) and for arbitrary ones (cancellation, reordering, ties)."""
     rng = np.random.default_rng(12)
     n_seq, length = 60_000, 18
-    v = rng.integers(-(1 << 29), (1 << 29) + 1, (n_seq, length)).astype(np.int32)
+    v = rng.integers(-(1 << 29), (1 << 29) + 1, (n_seq, length)).astype(np.int64)
+    v[::5] *= 1 << 8                                                                           # sums of INT32 products: up to 2^37
     v[rng.random((n_seq, length)) < 0.1] = 0
     small = rng.random((n_seq, length)) < 0.3
     v[small] = rng.integers(-40, 41, int(small.sum()))
@@ -237,3 +262,67 @@ def test_product_rounded_sum_on_host_equals_chain_of_fpu_additions(host_emu):
     # both phases are exercised: a good share of the additions in the integer phase, a good share after it
     share = exact_adds.value / (n_seq * length)
     assert 0.2 < share < 0.8
+
+
+def test_product_fixed_point_accumulator_on_host_equals_python_integers(host_emu):
+    """The exact accumulation mode's 192-bit sum and its single rounding against Python's unbounded integers and its
+    correctly rounded int -> float conversion: random terms over the whole window, terms below the unit (cut towards
+    minus infinity), cancellation down to a few bits, exact ties."""
+    rng = np.random.default_rng(44)
+    n_seq, length = 40_000, 24
+    v = rng.integers(-(1 << 36), (1 << 36) + 1, (n_seq, length)).astype(np.int64)
+    small = rng.random((n_seq, length)) < 0.4
+    v[small] = rng.integers(-(1 << 24), (1 << 24) + 1, int(small.sum()))
+    v[rng.random((n_seq, length)) < 0.1] = 0
+    sh = rng.integers(-80, 145, (n_seq, length)).astype(np.int32)
+    q = n_seq // 4
+    sh[:q] = np.minimum(144, np.cumsum(rng.integers(0, 9, (q, length)), axis=1))               # ascending ladders from the unit
+    sh[q:2 * q] = rng.integers(0, 3, (q, length))                                              # short sums: the exact branch
+    v[2 * q:2 * q + 3000, 1] = -v[2 * q:2 * q + 3000, 0]                                       # cancellation of the two
+    sh[2 * q:2 * q + 3000, 1] = sh[2 * q:2 * q + 3000, 0]                                      # largest terms
+    # exact ties: 2^60 + 2^7 has 54 significant bits, the last one is the half-way bit
+    v[-4:, :] = 0
+    sh[-4:, :] = 0
+    v[-4, 0], sh[-4, 0], v[-4, 1], sh[-4, 1] = 1, 60, 1, 7                                     # tie, even below: rounds down
+    v[-3, 0], sh[-3, 0], v[-3, 1], sh[-3, 1] = 1, 60, 3, 7                                     # tie, odd below: rounds up
+    v[-2, 0], sh[-2, 0], v[-2, 1], sh[-2, 1], v[-2, 2] = 1, 60, 1, 7, 1                        # just above the tie
+    v[-1, 0], sh[-1, 0], v[-1, 1], sh[-1, 1], v[-1, 2] = -1, 140, -1, 97, -1                   # negative, across all three words
+    unit = rng.integers(-400, 200, n_seq).astype(np.int32)
+    unit[-4:] = 0
+    words = np.empty((n_seq, 3), dtype=np.uint64)
+    out = np.empty(n_seq, dtype=np.uint64)
+    v, sh = np.ascontiguousarray(v), np.ascontiguousarray(sh)
+    host_emu.host_fixed192(v.ctypes.data_as(ctypes.c_void_p), sh.ctypes.data_as(ctypes.c_void_p), unit.ctypes.data_as(ctypes.c_void_p),
+                           words.ctypes.data_as(ctypes.c_void_p), out.ctypes.data_as(ctypes.c_void_p), ctypes.c_size_t(n_seq),
+                           ctypes.c_size_t(length))
+    vl, sl, wl = v.tolist(), sh.tolist(), words.tolist()
+    want = np.empty(n_seq, dtype=np.float64)
+    for i in range(n_seq):
+        total = 0
+        for x, h in zip(vl[i], sl[i]):
+            total += (x << h) if h >= 0 else (x >> -h)
+        got = wl[i][0] | (wl[i][1] << 64) | (wl[i][2] << 128)
+        assert got == total % (1 << 192), i
+        want[i] = float(total)                                       # correctly rounded, ties to even
+    want = np.ldexp(want, unit)
+    assert np.all(np.isfinite(want)) and not np.any((want != 0) & (np.abs(want) < 2.0 ** -1022))
+    assert np.array_equal(out, want.view(np.uint64))
+    assert want[-4] == 2.0 ** 60 and want[-3] == 2.0 ** 60 + 2.0 ** 9 and want[-2] == 2.0 ** 60 + 2.0 ** 8
+
+
+def test_contexts_are_created_selected_and_destroyed_on_the_host():
+    """Context plumbing that needs no GPU: a new context has no workspace, selecting it and the default context,
+    destroying it (also while it is current)."""
+    h1, h2 = lib.ozaki_context_create(), lib.ozaki_context_create()
+    assert h1 and h2 and h1 != h2
+    lib.ozaki_context_use(h1)
+    assert lib.ozaki_last_hip_error() == 0
+    f = lib.load().ozaki_dgemm
+    assert f(1, 1, 1, 1 << 20, 1, 1 << 20, 1, 1 << 20, 1, 0, 4, 0, 0) == lib.STATUS_WORKSPACE
+    lib.ozaki_context_use(h2)
+    lib.ozaki_context_destroy(h2)                      # current: the thread falls back to the default context
+    assert f(1, 1, 1, 1 << 20, 1, 1 << 20, 1, 1 << 20, 1, 0, 4, 0, 0) == lib.STATUS_WORKSPACE
+    lib.ozaki_context_use(None)
+    lib.ozaki_context_destroy(h1)
+    assert lib.load().ozaki_context_destroy(None) == -1
+    assert lib.load().ozaki_context_create(None) == -1

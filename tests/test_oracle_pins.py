@@ -94,25 +94,11 @@ def test_plan_bits_per_slice():
 
 
 # ------------------------------------------------------------------ Eq. 4-9: the split is error-free
-def _nasty_rows(rng, rows, k):
-    X = inputs.phi_matrix(rows, k, 3.0, rng)
-    X[0, :] = 0.0                                     # zero vector: c := 0
-    X[1, :] = 1.0                                     # max is a power of two
-    X[2, :] = np.nextafter(1.0, 2.0)                  # just above a power of two
-    X[3, :] = np.ldexp(rng.integers(-16, 17, k).astype(np.float64), -3)   # one-slice row
-    X[4, : k // 2] = 0.0
-    X[5, 0] = 2.0 ** 300
-    X[6, :] = inputs.full_mantissa_one_binade(1, k, rng)[0] * np.where(rng.random(k) < 0.5, -1, 1)
-    X[7, :] *= 2.0 ** -400
-    # ties: entries exactly half way between two slice values of the first slice
-    X[8, :] = 0.0
-    X[8, 0] = 1.0
-    X[8, 1:9] = (2 * np.arange(8) + 1) / 32.0         # odd multiples of 2^-5 when the first ulp is 2^-4
-    return X
+_nasty_rows = inputs.nasty_rows
 
 
 @pytest.mark.parametrize("fmt,k", [("fp8", 64), ("fp16", 64), ("fp16", 1024), ("fp8", 4096), ("fp6", 64), ("fp6", 4096),
-                                   ("fp6_e3m2", 64), ("fp6_e3m2", 4096)])
+                                   ("fp6_e3m2", 64), ("fp6_e3m2", 4096), ("int8", 64), ("int8", 4096)])
 def test_slices_sum_back_exactly_and_fit_their_format(fmt, k):
     rng = np.random.default_rng(11)
     X = _nasty_rows(rng, 12, k)
@@ -124,8 +110,8 @@ def test_slices_sum_back_exactly_and_fit_their_format(fmt, k):
         q = np.ldexp(sl[p], b)
         assert np.array_equal(q, np.rint(q))                      # integer multiples of 2^-b
         assert np.max(np.abs(q)) <= 2 ** b                        # inside [-1, 1]
-        codes = formats.encode_exact(fmt, sl[p])                  # representable in Type2 ...
-        assert np.array_equal(formats.decode(fmt, codes), sl[p])  # ... and round-trips
+        codes = formats.encode_exact(fmt, sl[p], b)               # representable in Type2 ...
+        assert np.array_equal(formats.decode(fmt, codes, b), sl[p])   # ... and round-trips
     # remainder after slice p is at most half an ulp of that slice
     sl1, cs1, rem1 = oz.slice_rows(X, plan.rho, 1)
     assert np.all(np.abs(rem1) <= np.ldexp(1.0, cs1[0] - b - 1)[:, None])
@@ -258,7 +244,8 @@ def _exact_sum_of_terms(blocks, b):
     return tot
 
 
-@pytest.mark.parametrize("fmt,kblock", [("fp8", 0), ("fp16", 0), ("fp8", 16), ("fp16", 10), ("fp6", 0), ("fp6", 16), ("fp6_e3m2", 0)])
+@pytest.mark.parametrize("fmt,kblock", [("fp8", 0), ("fp16", 0), ("fp8", 16), ("fp16", 10), ("fp6", 0), ("fp6", 16), ("fp6_e3m2", 0),
+                                        ("int8", 0), ("int8", 16)])
 def test_all_slices_all_pairs_equal_the_exact_product(fmt, kblock):
     """Eq. 10 with every slice and every pair is an identity: brute force on tiny, non-square inputs."""
     rng = np.random.default_rng(21)
@@ -296,6 +283,14 @@ def test_pair_products_stay_inside_the_exact_fp32_window():
     assert np.array_equal(np.abs(P), np.full((2, 2), 1 << 24))
     assert np.array_equal(np.float32(P).astype(np.int64), P)       # representable in FP32
     assert np.array_equal(C, A @ B)
+    # INT8 slices with INT32 accumulation: |q| <= 64, exact while k * 4^6 <= 2^31 - 1; one index more costs a slice bit
+    assert oz.make_plan(524287, "int8").b == 6 and oz.make_plan(524288, "int8").b == 5
+    k = 4096
+    C, blocks = oz.ozaki_dgemm(np.ones((1, k)), -np.ones((k, 1)), "int8", 1, 0, return_blocks=True)
+    assert int(blocks[0].products[0][0, 0]) == -k * 4096 and C[0, 0] == -k
+    assert formats.int8_encode_exact(np.array([-1.0, 1.0, 0.5, -1 / 64]), 6).tolist() == [0xC0, 0x40, 0x20, 0xFF]
+    with pytest.raises(ValueError):
+        formats.int8_encode_exact(np.array([2.0]), 6)               # 128 does not fit a signed byte
     # k-blocking keeps FP16 slices inside the window as well
     k = 4096
     C, blocks = oz.ozaki_dgemm(np.ones((1, k)), np.ones((k, 1)), "fp16", 1, 1024, return_blocks=True)
@@ -581,3 +576,31 @@ def test_exact_reference_is_exact():
     assert exact.exact_dot(x2, y2) == Fraction(N * (N + 1) * (N + 2), 6)
     assert exact.exact_dot(np.array([0.1]), np.array([0.1])) == Fraction(0.1) * Fraction(0.1)
     assert exact.exact_dot(np.array([-0.1, 3.0]), np.array([0.1, 1.0]), absolute=True) == Fraction(0.1) * Fraction(0.1) + 3
+
+
+def test_fast_exact_residuals_agree_with_big_integers():
+    """exact.dot_residuals (halves of 26 bits, math.fsum) against the big-integer exact_dot: the residual c_hat - x.y
+    and the product itself, both rounded once, on wide-range, cancelling and benchmark-like vectors."""
+    rng = np.random.default_rng(404)
+    cases = []
+    for phi, k in ((0.5, 300), (4.0, 1000), (2.0, 4096)):
+        cases.append((inputs.phi_matrix(1, k, phi, rng)[0], inputs.phi_matrix(1, k, phi, rng)[0]))
+    x = inputs.full_mantissa_one_binade(1, 512, rng)[0]
+    cases.append((np.concatenate([x, -x]), np.concatenate([x[::-1], x[::-1]]) * (1 + 2.0 ** -30)))      # heavy cancellation
+    cases.append((np.array([2.0 ** 500, 1.0, -(2.0 ** 500)]), np.array([2.0 ** 300, 3.0, 2.0 ** 300])))
+    for x, y in cases:
+        ex = exact.exact_dot(x, y)
+        for c_hat in (float(x @ y), exact.round_fraction_to_double(ex), 0.0, 1.25 * float(x @ y) + 1e-300):
+            res, dot = exact.dot_residuals(x, y, c_hat)
+            assert res == exact.round_fraction_to_double(Fraction(c_hat) - ex)
+            assert dot == exact.round_fraction_to_double(ex)
+    A, B = inputs.phi_pair(6, 5, 700, 3.0, seed=8)
+    ent = [(i, j) for i in range(6) for j in range(5)]
+    C = A @ B
+    slow = exact.sampled_errors(A, B, ent, [C[i, j] for i, j in ent])
+    fast = exact.sampled_errors_fast(A, B, ent, [C[i, j] for i, j in ent])
+    assert np.allclose(slow[2], fast[2], rtol=1e-9, atol=0) and np.allclose(slow[3], fast[3], rtol=1e-9, atol=0)
+    # distance in units in the last place
+    a = np.array([1.0, 1.0, -0.0, -1.0, 2.0 ** -1074])
+    b = np.array([np.nextafter(1.0, 2.0), np.nextafter(np.nextafter(1.0, 0.0), 0.0), 0.0, 1.0, -(2.0 ** -1074)])
+    assert list(exact.ulp_distance(a, b)) == [1, 2, 0, 2 * 0x3FF0000000000000, 2]
