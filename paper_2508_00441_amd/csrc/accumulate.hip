@@ -51,17 +51,18 @@ struct AccArgs {
     int read_S, write_S, add_to_C;
     int allow_chain;         // the GEMM kernel summed tile-wide runs
     int merge;               // rule "runs": merge equal-scale products of an anti-diagonal element by element
-    const int32_t* da;       // deltas of the block: [rows_pad_a / 32][s]
-    const int32_t* db;       // [rows_pad_b / 32][s]
+    const int32_t* da;       // deltas of the block: [s][rows_pad_a / 32]
+    const int32_t* db;       // [s][rows_pad_b / 32]
     PairOrder order;
     Pass pass;
 };
 
 // Is pair `pos` of anti-diagonal g (0-based position) stored on its own, i.e. does it start a run of the GEMM kernel?
-// dA / dB: the delta rows of the 32 rows / 32 columns concerned; p, q 0-based slice indices of the pair.
-__device__ __forceinline__ bool starts_run(const PairOrder& o, int allow_chain, const int32_t* dA, const int32_t* dB, int pos, int p,
-                                           int q) {
-    return pos % o.run_limit == 0 || !(allow_chain && pair_linked(dA, dB, p - 1, q + 1));
+// dA / dB: the block's deltas advanced to the group of the 32 rows / 32 columns concerned, ga / gb: groups per slice;
+// p, q 0-based slice indices of the pair.
+__device__ __forceinline__ bool starts_run(const PairOrder& o, int allow_chain, const int32_t* dA, int64_t ga, const int32_t* dB,
+                                           int64_t gb, int pos, int p, int q) {
+    return pos % o.run_limit == 0 || !(allow_chain && pair_linked(dA, ga, dB, gb, p - 1, q + 1));
 }
 
 template <int MODE, bool PINT>
@@ -124,8 +125,9 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
     // the whole position) to the pair before it inside its group.  Built by the first wave, one anti-diagonal at a time
     // (an anti-diagonal has at most 32 pairs).
     if (tid < 64) {
-        const int32_t* dA = a.da + (size_t)(m0 / LINK_ROWS) * a.order.s;
-        const int32_t* dB = a.db + (size_t)(n0 / LINK_ROWS) * a.order.s;
+        const int64_t ga = a.rows_pad_a / LINK_ROWS, gb = a.rows_pad_b / LINK_ROWS;
+        const int32_t* dA = a.da + m0 / LINK_ROWS;
+        const int32_t* dB = a.db + n0 / LINK_ROWS;
         int count = 0, slot0 = 0;
         for (int g = a.pass.g_hi; g >= a.pass.g_lo; --g) {
             const int len = diag_len(a.order, g);
@@ -134,7 +136,7 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
             if (tid < len) {
                 const int p = diag_first_p(a.order, g) + tid - 1, q = g - p - 2;     // 0-based slice indices
                 const bool first = tid == 0;                                        // first pair of the anti-diagonal: ends every run
-                start = starts_run(a.order, a.allow_chain, dA, dB, tid, p, q);      // stored on its own
+                start = starts_run(a.order, a.allow_chain, dA, ga, dB, gb, tid, p, q);      // stored on its own
                 entry = (uint32_t)(slot0 + tid) | ((uint32_t)p << 12) | ((uint32_t)q << 18) | ((uint32_t)first << 24);
             }
             const unsigned long long mask = __ballot(start);
@@ -244,6 +246,7 @@ struct ExportArgs {
     int allow_chain;
     const int32_t* da;
     const int32_t* db;
+    int64_t ga, gb;          // groups of 32 vectors per slice in da / db
     PairOrder order;
     Pass pass;
 };
@@ -262,12 +265,12 @@ __global__ void __launch_bounds__(256) export_products_kernel(const ExportArgs a
         acc_order_to_mn(idx, ml, nl);
         const int64_t mi = (int64_t)tm * TILE + ml, nj = (int64_t)tn * TILE + nl;
         if (mi >= a.m || nj >= a.n) continue;
-        const int32_t* dA = a.da + (size_t)(mi / LINK_ROWS) * a.order.s;
-        const int32_t* dB = a.db + (size_t)(nj / LINK_ROWS) * a.order.s;
+        const int32_t* dA = a.da + mi / LINK_ROWS;
+        const int32_t* dB = a.db + nj / LINK_ROWS;
         int run = 0;
-        if (starts_run(a.order, a.allow_chain, dA, dB, pos, p, q)) {
+        if (starts_run(a.order, a.allow_chain, dA, a.ga, dB, a.gb, pos, p, q)) {
             run = 1;
-            while (pos + run < len && !starts_run(a.order, a.allow_chain, dA, dB, pos + run, p + run, q - run)) ++run;
+            while (pos + run < len && !starts_run(a.order, a.allow_chain, dA, a.ga, dB, a.gb, pos + run, p + run, q - run)) ++run;
         }
         const size_t o = ((size_t)z * a.n + nj) * a.m + mi;
         const uint32_t w = reinterpret_cast<const uint32_t*>(a.P)[(size_t)z * pair_stride + gi];
@@ -367,6 +370,7 @@ hipError_t launch_export_products(const Plan& pl, const Operand& A, const Operan
     a.allow_chain = chained ? 1 : 0;
     a.da = A.deltas + (size_t)t * (A.rows_pad / LINK_ROWS) * pl.s;
     a.db = B.deltas + (size_t)t * (B.rows_pad / LINK_ROWS) * pl.s;
+    a.ga = A.rows_pad / LINK_ROWS; a.gb = B.rows_pad / LINK_ROWS;
     a.order = order; a.pass = ps;
     dim3 grid(grid_for(pl.tiles_m * pl.tiles_n * (int64_t)TILE_ELEMS), (unsigned)ps.npairs);
     hipLaunchKernelGGL(export_products_kernel, grid, dim3(256), 0, st, a);

@@ -46,9 +46,9 @@ struct Operand {
     int64_t rows_pad;     // multiple of TILE
     uint8_t* slices;      // [T][s][chunks][rows_pad][row_bytes]
     int32_t* exps;        // [T][s][rows_pad]   exponent c of Eq. 4 (0 for padding vectors)
-    int32_t* deltas;      // [T][rows_pad/LINK_ROWS][s]  per group of 32 vectors (one matrix-unit tile edge) and slice p:
+    int32_t* deltas;      // [T][s][rows_pad/LINK_ROWS]  per slice p and group of 32 vectors (one matrix-unit tile edge):
                           //                        c_p - c_(p+1) if that difference is the same for all real vectors of
-                          //                        the group, else DELTA_IRREGULAR
+                          //                        the group, else DELTA_IRREGULAR (always for the last slice)
 };
 
 constexpr int LINK_ROWS = 32;             // granularity of the equal-scale decision: one 32 x 32 matrix-unit tile
@@ -136,11 +136,13 @@ __host__ __device__ inline Group pass_group(const PairOrder& o, const Pass& ps, 
 
 // True if, for every element of a 32 x 32 tile, pair (p+1, q-1) carries the same scale factor 2^(cA + cB) as pair
 // (p, q) (0-based slice indices): then the two products can be summed in the accumulator of the matrix unit
-// (a group has at most run_limit pairs, so the sum stays inside the exact window).  dA / dB: the rows of
-// Operand::deltas of the tile's 32 rows of A and 32 columns of B.
-__host__ __device__ inline bool pair_linked(const int32_t* dA, const int32_t* dB, int p, int q) {
-    const int a = dA[p], b = dB[q - 1];
-    return a != DELTA_IRREGULAR && a == b;
+// (a group has at most run_limit pairs, so the sum stays inside the exact window).  a: the delta of slice p of the
+// tile's 32 rows of A, b: the delta of slice q - 1 of its 32 columns of B.
+__host__ __device__ inline bool deltas_link(int a, int b) { return a != DELTA_IRREGULAR && a == b; }
+// dA / dB: Operand::deltas of the block, advanced to the tile's group of rows of A / columns of B; ga / gb: groups per
+// slice (rows_pad / LINK_ROWS) of the two operands.
+__host__ __device__ inline bool pair_linked(const int32_t* dA, int64_t ga, const int32_t* dB, int64_t gb, int p, int q) {
+    return deltas_link(dA[p * ga], dB[(q - 1) * gb]);
 }
 
 // ---- pair-product storage ("accumulator order") ------------------------------------------------------------

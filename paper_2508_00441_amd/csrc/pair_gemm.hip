@@ -60,8 +60,8 @@ struct GemmArgs {
     int64_t chunks;
     int tiles_m, tiles_n;
     int allow_chain;
-    const int32_t* da;       // A deltas of the block: [rows_pad_a / 32][s]
-    const int32_t* db;       // B deltas of the block: [rows_pad_b / 32][s]
+    const int32_t* da;       // A deltas of the block: [s][rows_pad_a / 32]
+    const int32_t* db;       // B deltas of the block: [s][rows_pad_b / 32]
     PairOrder order;
     Pass pass;
 };
@@ -116,27 +116,26 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
     // when pair jp is complete: it does if all 32 rows of A and all 32 columns of B behind the tile carry the same scale
     // factor for both pairs (pair_linked; the sum stays inside the exact window because a group has at most run_limit
     // pairs).  The rows of A behind tile column j are the 32-vector group tm*8 + wm*4 + j, the columns of B behind
-    // tile row i the group tn*8 + wn*4 + i.  The delta rows are read through the scalar cache (they were written by an
-    // earlier kernel and the addresses are wave-uniform), so they stay out of the vector-memory counter that paces
-    // the load ring.
-    typedef const __attribute__((address_space(4))) int32_t* delta_ptr;
-    const int nslices = a.order.s;
-    const delta_ptr dA = (delta_ptr)(a.da + (size_t)(tm * 8 + wm * 4) * nslices);
-    const delta_ptr dB = (delta_ptr)(a.db + (size_t)(tn * 8 + wn * 4) * nslices);
+    // tile row i the group tn*8 + wn*4 + i.  The deltas of the wave's four groups are 16 contiguous bytes per slice and
+    // are read through the scalar cache (they were written by an earlier kernel and the addresses are wave-uniform), so
+    // they stay out of the vector-memory counter that paces the load ring.
+    typedef int v4s __attribute__((ext_vector_type(4)));
+    typedef const __attribute__((address_space(4))) v4s* delta4_ptr;
+    const int64_t groups_a = a.rows_pad_a / LINK_ROWS, groups_b = a.rows_pad_b / LINK_ROWS;
+    // the four consecutive groups of this wave, for slice 0: 16 bytes, 16-byte aligned (slice p follows p * groups later)
+    const int32_t* const dA = a.da + (tm * 8 + wm * 4);
+    const int32_t* const dB = a.db + (tn * 8 + wn * 4);
     // bit i*4+j: tile (i, j) continues its run after pair jp (0-based position in the group)
     auto continue_mask = [&](int jp) -> unsigned {
         if (!a.allow_chain) return 0u;
-        int dav[4], dbv[4];
-#pragma unroll
-        for (int t4 = 0; t4 < 4; ++t4) {
-            dav[t4] = __builtin_amdgcn_readfirstlane(dA[t4 * nslices + p0 + jp]);
-            dbv[t4] = __builtin_amdgcn_readfirstlane(dB[t4 * nslices + q0 - jp - 1]);
-        }
+        const v4s dav = *(delta4_ptr)(dA + (size_t)(p0 + jp) * groups_a);
+        const v4s dbv = *(delta4_ptr)(dB + (size_t)(q0 - jp - 1) * groups_b);
         unsigned cont = 0;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) cont |= (dav[j] != DELTA_IRREGULAR && dav[j] == dbv[i]) ? (1u << (i * 4 + j)) : 0u;
+            for (int j = 0; j < 4; ++j)
+                cont |= deltas_link(__builtin_amdgcn_readfirstlane(dav[j]), __builtin_amdgcn_readfirstlane(dbv[i])) ? (1u << (i * 4 + j)) : 0u;
         return cont;
     };
 
@@ -186,13 +185,16 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) t[r] = 0;
     };
-    // the wave's part of the product slot `slot`, MFMA tile (i, j): 4 KiB contiguous, 16 bytes per lane and quarter
+    // the wave's part of the product slot `slot`, MFMA tile (i, j): 4 KiB contiguous, 16 bytes per lane and quarter.
+    // The tile's base address is wave-uniform (it stays in scalar registers), the lane adds a 32-bit byte offset.
+    const unsigned lane_bytes = (unsigned)lane * 16u;
     auto store_tile = [&](int slot, int i, int j, const acc_t& t) {
-        float* out = a.P + ((size_t)(slot * a.tiles_n + tn) * a.tiles_m + tm) * TILE_ELEMS + (size_t)wave * 16384 + lane * 4;
+        char* base = reinterpret_cast<char*>(a.P + ((size_t)(slot * a.tiles_n + tn) * a.tiles_m + tm) * TILE_ELEMS + (size_t)wave * 16384 +
+                                             (size_t)(i * 4 + j) * 1024);
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
             acc4_t v = {t[4 * g4], t[4 * g4 + 1], t[4 * g4 + 2], t[4 * g4 + 3]};
-            *reinterpret_cast<acc4_t*>(out + ((i * 4 + j) * 4 + g4) * 256) = v;
+            *reinterpret_cast<acc4_t*>(base + g4 * 1024 + lane_bytes) = v;
         }
     };
 
@@ -325,6 +327,10 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
     const std::integral_constant<int, 1> c1;
     unsigned run_start[4] = {0u, 0u, 0u, 0u};           // byte j of word i: first pair of the run tile (i, j) is accumulating
     for (int jp = 0; jp < glen; ++jp) {
+        // which tiles continue their run after this pair: the scalar loads behind this are issued now and have long
+        // landed when the pair's last stage is done
+        const bool last_pair = jp + 1 == glen;
+        const unsigned cont = last_pair ? 0u : continue_mask(jp);
         if constexpr (KS == 1) {
             int c = 0;
             for (; c + 1 < chunks; c += 2) {
@@ -349,8 +355,6 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
         }
         // The pair is complete.  Every tile whose run the next pair does not continue is stored to the slot of the
         // run's first pair and cleared (the stores only make the next vmcnt wait stricter).
-        const bool last_pair = jp + 1 == glen;
-        const unsigned cont = last_pair ? 0u : continue_mask(jp);
         if (cont != 0xFFFFu) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -358,7 +362,7 @@ __global__ void __launch_bounds__(256) pair_gemm_kernel(const GemmArgs a) {
                 for (int j = 0; j < 4; ++j)
                     if (!((cont >> (i * 4 + j)) & 1u)) {
                         store_tile(grp.slot + (int)((run_start[i] >> (8 * j)) & 0xFFu), i, j, acc[i][j]);
-                        if (!last_pair) zero_tile(acc[i][j]);
+                        zero_tile(acc[i][j]);
                         run_start[i] = (run_start[i] & ~(0xFFu << (8 * j))) | ((unsigned)(jp + 1) << (8 * j));
                     }
         }

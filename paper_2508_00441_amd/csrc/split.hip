@@ -124,8 +124,13 @@ __device__ __forceinline__ void decode_element(uint64_t w, int F, int64_t& tv, i
 // ceil(log2 |x|) of the still dormant ones (cdorm).  rescale: left shift that brings an active remainder from the
 // previous slice's unit to this one.  WIDE: the format has slices of more than 7 bits (FP16 only).
 template <bool WIDE>
-__device__ __forceinline__ int slice_element(int64_t& T, int& st, int unit, int rescale, int F, int64_t round_bias, uint64_t& rmax,
+__device__ __forceinline__ int slice_element(int64_t& tv, int& pk, int unit, int rescale, int F, int64_t round_bias, uint64_t& rmax,
                                              int& cdorm) {
+    // Divergent branches on purpose: dormant elements (most of a wide-range vector during its first slices) and zeros
+    // skip the 64-bit arithmetic altogether, which a select-only form would execute for every element (measured:
+    // 2.9 ms instead of 2.1 ms for the slicing of two 8192 x 8192 operands).
+    int64_t T = tv;
+    const int st = pk;
     int q = 0;
     bool active = st == ACTIVE;
     if (active) {
@@ -134,7 +139,7 @@ __device__ __forceinline__ int slice_element(int64_t& T, int& st, int unit, int 
         const int ef = (int)(short)(st & 0xFFFF);
         if (unit <= ef) {                                  // representable now: x / 2^unit * 2^F
             T <<= (ef - unit);
-            st = ACTIVE;
+            pk = ACTIVE;
             active = true;
         } else if (WIDE && unit - ef + F <= 53) {
             // Wide slices only (b >= 8, fewer than 53 fraction bits): the element reaches the unit but its
@@ -144,13 +149,14 @@ __device__ __forceinline__ int slice_element(int64_t& T, int& st, int unit, int 
             const int64_t q64 = (T + (((int64_t)1 << (sh - 1)) - 1) + ((T >> sh) & 1)) >> sh;
             q = (int)q64;
             T -= q64 << sh;
+            tv = T;
             const uint64_t ar = (uint64_t)(T < 0 ? -T : T);
             if (ar == 0) {
-                st = ACTIVE;                               // nothing left: an active zero
+                pk = ACTIVE;                               // nothing left: an active zero
             } else {
                 const int L = 64 - __clzll((long long)ar);
                 const int cd = ef - F + L - (((ar & (ar - 1)) == 0) ? 1 : 0);
-                st = (st & 0xFFFF) | (cd << 16);
+                pk = (st & 0xFFFF) | (cd << 16);
                 cdorm = cd > cdorm ? cd : cdorm;
             }
         } else {
@@ -165,6 +171,7 @@ __device__ __forceinline__ int slice_element(int64_t& T, int& st, int unit, int 
         T -= q64 << F;
         const uint64_t ar = (uint64_t)(T < 0 ? -T : T);
         rmax = ar > rmax ? ar : rmax;
+        tv = T;
     }
     return q;
 }
@@ -502,16 +509,16 @@ __global__ void __launch_bounds__(256) delta_kernel(DeltaOperand o0, DeltaOperan
     const int64_t group = row / LINK_ROWS;
     const int lane = threadIdx.x & 63, half = lane & 32;
     const int32_t* e = exps + (size_t)t * s * rows_pad;
-    int32_t* out = deltas + ((size_t)t * groups + group) * s;
+    int32_t* out = deltas + (size_t)t * s * groups + group;          // slice p of this group at out[p * groups]
     for (int p = 0; p + 1 < s; ++p) {
         const int d = e[(size_t)p * rows_pad + row] - e[(size_t)(p + 1) * rows_pad + row];
         // the first vector of a group is a real one, or the whole group is padding (then every d is 0)
         const int ref = __shfl(d, half, 64);
         const unsigned long long ok = __ballot(row >= rows || d == ref);
         const bool same = (uint32_t)(ok >> half) == 0xFFFFFFFFu;
-        if ((lane & 31) == 0) out[p] = same ? ref : DELTA_IRREGULAR;
+        if ((lane & 31) == 0) out[(size_t)p * groups] = same ? ref : DELTA_IRREGULAR;
     }
-    if ((lane & 31) == 0) out[s - 1] = DELTA_IRREGULAR;
+    if ((lane & 31) == 0) out[(size_t)(s - 1) * groups] = DELTA_IRREGULAR;
 }
 
 template <int U, int TPR>

@@ -108,6 +108,11 @@ NUM_SLICES = {
     "c4_16384_fp16_kb1024": 8, "c4_16384_fp16_kb4096": 9, "c4_16384_fp8": 13,
     "c5a_16384x1024_fp8": 13, "c5b_1024x65536_fp8": 13,
 }
+#: the same for INT8 slices (b = 6: seven bits of progress per slice instead of five), lines "<config>@int8" of the fixture
+NUM_SLICES_INT8 = {
+    "c1_256_fp8_hw": 9, "c2_4096_fp8_hw": 9, "c3_8192_fp8_emu": 11, "c4_16384_fp8": 9,
+    "c5a_16384x1024_fp8": 9, "c5b_1024x65536_fp8": 10,
+}
 S_BOUND = {
     "c1_256_fp8_hw": 10, "c2_4096_fp8_hw": 10, "c3_8192_fp8_emu": 13,
     "c4_16384_fp16_kb1024": 6, "c4_16384_fp16_kb4096": 7, "c4_16384_fp8": 9,

@@ -7,8 +7,9 @@ product on sampled entries:
   s_bound   smallest s whose max |C_hat - C*| / (|A||B|) is <= 4 k 2^-53   (the stated bound)
   s_native  smallest s whose error is <= that of a plain FP64 GEMM (numpy) on the same entries
 
-Usage:  python tests/golden/calibrate_slices.py [config ...]      -> tests/golden/slices_per_config.txt
-Calls nothing but oracle/ and the input generators.
+Usage:  python tests/golden/calibrate_slices.py [config[@format] ...]      -> tests/golden/slices_per_config.txt
+A name like c3_8192_fp8_emu@int8 calibrates the configuration with another slice format.  Lines of configurations that
+are not named on the command line are kept.  Calls nothing but oracle/ and the input generators.
 """
 from __future__ import annotations
 
@@ -40,6 +41,8 @@ def sample_operands(cfg):
 
 
 def calibrate(name, cfg):
+    if "@" in name:
+        cfg = dict(cfg, fmt=name.split("@")[1])
     As, Bs = sample_operands(cfg)
     k = cfg["k"]
     rng = np.random.default_rng(7)
@@ -63,17 +66,23 @@ def calibrate(name, cfg):
 
 def main(argv):
     names = argv or list(inputs.CONFIGS)
-    lines = ["# Slices per benchmark configuration, calibrated with the CPU oracle against the exact big-integer product",
-             f"# on {NENTRIES} entries of a {NSAMPLE} x {NSAMPLE} sample of rows/columns (written by calibrate_slices.py).",
-             "# config  s_bound  s_native  bound(4k2^-53)  native_E_AB  native_E_C  | sweep s:E_AB ..."]
+    header = ["# Slices per benchmark configuration, calibrated with the CPU oracle against the exact big-integer product",
+              f"# on {NENTRIES} entries of a {NSAMPLE} x {NSAMPLE} sample of rows/columns (written by calibrate_slices.py).",
+              "# config  s_bound  s_native  bound(4k2^-53)  native_E_AB  native_E_C  | sweep s:E_AB ..."]
+    kept = {}
+    if os.path.exists(OUT):
+        with open(OUT) as f:
+            for line in f:
+                if line.strip() and not line.startswith("#"):
+                    kept[line.split()[0]] = line.rstrip("\n")
     for name in names:
         t0 = time.time()
-        r = calibrate(name, inputs.CONFIGS[name])
+        r = calibrate(name, inputs.CONFIGS[name.split("@")[0]])
         sweep = " ".join(f"{s}:{e:.2e}" for s, e, _ in r["sweep"])
-        lines.append(f"{name} {r['s_bound']} {r['s_native']} {r['bound']:.3e} {r['native_e_ab']:.3e} {r['native_e_c']:.3e} | {sweep}")
-        print(lines[-1], f"({time.time() - t0:.0f} s)", flush=True)
+        kept[name] = f"{name} {r['s_bound']} {r['s_native']} {r['bound']:.3e} {r['native_e_ab']:.3e} {r['native_e_c']:.3e} | {sweep}"
+        print(kept[name], f"({time.time() - t0:.0f} s)", flush=True)
     with open(OUT, "w") as f:
-        f.write("\n".join(lines) + "\n")
+        f.write("\n".join(header + list(kept.values())) + "\n")
 
 
 if __name__ == "__main__":

@@ -12,9 +12,15 @@ def test_num_slices_table_matches_calibration_file(golden_dir):
                 continue
             name, s_bound, s_native = line.split()[:3]
             seen[name] = (int(s_bound), int(s_native))
+    int8 = {name.split("@")[0]: v for name, v in seen.items() if name.endswith("@int8")}
+    seen = {name: v for name, v in seen.items() if "@" not in name}
     assert set(seen) == set(inputs.CONFIGS) == set(inputs.NUM_SLICES) == set(inputs.S_BOUND)
     for name, (sb, sn) in seen.items():
         assert inputs.S_BOUND[name] == sb and inputs.NUM_SLICES[name] == sn, name
+    # the same workloads with INT8 slices (lines "<config>@int8")
+    assert set(int8) == set(inputs.NUM_SLICES_INT8)
+    for name, (sb, sn) in int8.items():
+        assert inputs.NUM_SLICES_INT8[name] == sn, name
 
 
 def test_paper_workload_uses_the_slice_counts_of_table_2(golden_dir):
