@@ -60,7 +60,7 @@ enum {
                                   /* round-to-nearest-even, bitwise equal to the hardware result        */
     OZAKI_ACCUM_EXACT_FIXED = 2   /* integer-only as well: the terms of a block are summed without any  */
                                   /* rounding in a 192-bit fixed-point integer per element (the sum of  */
-                                  /* Eq. 10 "without rounding errors", remark after Eq. 11) and rounded */
+                                  /* Eq. 10 free of rounding error, remark after Eq. 11) and rounded   */
                                   /* to FP64 once.  Unit: 2^-144 of the unit of the leading pair's      */
                                   /* product; a term whose scale lies further down is cut to that unit  */
                                   /* towards minus infinity.  Block sums are added to C with the        */
@@ -285,7 +285,7 @@ int ozaki_split(int is_B, int64_t rows, int64_t k, const double* X, int64_t ldx,
                 void* slices_out, int32_t* exps_out);
 
 /*
- * ozaki_count_slices -- how many slices Eq. 4-8 extract from an operand "until x^(p) = 0" (Section 3, the
+ * ozaki_count_slices -- how many slices Eq. 4-8 extract from an operand until its remainder is zero (Section 3, the
  * paragraph before Eq. 4): the largest count over its vectors and k-blocks.  With that many slices (the larger
  * of the two operands' counts) and OZAKI_PAIRS_ALL the sum of the pair products is the exact product, which is
  * the error-free setting of the paper.

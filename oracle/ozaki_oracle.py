@@ -147,7 +147,8 @@ def slice_rows(X: np.ndarray, rho: int, num_slices: int):
 
 
 def slice_to_exhaustion(X: np.ndarray, rho: int, max_slices: int = 4096):
-    """Eq. 4-8 'until x^(p) = 0' (paragraph before Eq. 4): slices until every row's remainder is zero."""
+    """Eq. 4-8 repeated until the remainder vanishes (the stopping rule of the paragraph before Eq. 4): slices until
+    every row's remainder is zero."""
     x = np.array(X, dtype=np.float64, copy=True)
     slices, cs = [], []
     while np.any(x != 0):
@@ -271,7 +272,7 @@ _to_float_rne = np.frompyfunc(float, 1, 1)             # Python's int -> float c
 
 
 def _accumulate_exact(terms, e_lead, shape):
-    """Variant: the sum of Eq. 10 "performed without rounding errors" (remark after Eq. 11) as far as a fixed-point
+    """Variant: the sum of Eq. 10 carried out free of rounding error (remark after Eq. 11) as far as a fixed-point
     integer reaches, rounded to FP64 once.  Per element the unit is 2^(e_lead - EXACT_WINDOW_BITS), e_lead being the
     scale exponent of the leading pair (1,1); a term whose scale lies more than EXACT_WINDOW_BITS below e_lead is
     cut to that unit towards minus infinity (it is below 2^-128 of the leading product's unit), every other term

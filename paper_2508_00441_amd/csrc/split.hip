@@ -126,28 +126,23 @@ __device__ __forceinline__ void decode_element(uint64_t w, int F, int64_t& tv, i
 template <bool WIDE>
 __device__ __forceinline__ int slice_element(int64_t& tv, int& pk, int unit, int rescale, int F, int64_t round_bias, uint64_t& rmax,
                                              int& cdorm) {
-    // Divergent branches on purpose: dormant elements (most of a wide-range vector during its first slices) and zeros
-    // skip the 64-bit arithmetic altogether, which a select-only form would execute for every element (measured:
-    // 2.9 ms instead of 2.1 ms for the slicing of two 8192 x 8192 operands).
-    int64_t T = tv;
+    // The bookkeeping of dormant elements is done with selects, the 64-bit arithmetic of active ones behind ONE
+    // divergent branch: dormant elements (most of a wide-range vector during its first slices) and zeros skip it.
+    // (A select-only form runs the arithmetic for every element: 2.9 instead of 2.0 ms for two 8192 x 8192 operands;
+    // nested branches cost more scalar instructions than the selects.)
     const int st = pk;
-    int q = 0;
-    bool active = st == ACTIVE;
-    if (active) {
-        T <<= rescale;
-    } else {
-        const int ef = (int)(short)(st & 0xFFFF);
-        if (unit <= ef) {                                  // representable now: x / 2^unit * 2^F
-            T <<= (ef - unit);
-            pk = ACTIVE;
-            active = true;
-        } else if (WIDE && unit - ef + F <= 53) {
+    const bool was_active = st == ACTIVE;
+    const int ef = (int)(short)(st & 0xFFFF);
+    const bool wakes = !was_active && unit <= ef;          // representable from now on: x / 2^unit * 2^F
+    const bool active = was_active || wakes;
+    if constexpr (WIDE) {
+        if (!active && unit - ef + F <= 53) {
             // Wide slices only (b >= 8, fewer than 53 fraction bits): the element reaches the unit but its
             // low bits do not fit the fixed-point form yet.  Round its integer form tv * 2^E directly, by
             // sh = unit - E bits, and let the remainder wait on as a dormant element with the same E.
+            int64_t T = tv;
             const int sh = unit - ef + F;                  // F < sh <= 53
             const int64_t q64 = (T + (((int64_t)1 << (sh - 1)) - 1) + ((T >> sh) & 1)) >> sh;
-            q = (int)q64;
             T -= q64 << sh;
             tv = T;
             const uint64_t ar = (uint64_t)(T < 0 ? -T : T);
@@ -159,12 +154,16 @@ __device__ __forceinline__ int slice_element(int64_t& tv, int& pk, int unit, int
                 pk = (st & 0xFFFF) | (cd << 16);
                 cdorm = cd > cdorm ? cd : cdorm;
             }
-        } else {
-            const int cd = st >> 16;
-            cdorm = cd > cdorm ? cd : cdorm;               // |x| < 2^(unit-1): q = 0, remainder = x
+            return (int)q64;
         }
     }
+    const int cd = st >> 16;
+    cdorm = (!active && cd > cdorm) ? cd : cdorm;          // still dormant: |x| < 2^(unit-1), q = 0, remainder = x
+    pk = active ? ACTIVE : st;
+    int q = 0;
     if (active) {
+        // an active remainder is rescaled from the previous slice's unit, a waking element is brought to this unit
+        int64_t T = tv << (was_active ? rescale : ef - unit);
         // nearest integer to T / 2^F, ties to even (two's complement form), and the exact remainder
         const int64_t q64 = (T + round_bias + ((T >> F) & 1)) >> F;
         q = (int)q64;
@@ -315,7 +314,7 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
             }
         }
         if (v_slices == nullptr) {
-            // count-only mode ("until x^(p) = 0", paragraph before Eq. 4): something is left before the (p+1)-th
+            // count-only mode (slicing until the remainder is zero, paragraph before Eq. 4): something is left before the (p+1)-th
             // slice, so this vector needs at least p + 1 of them
             if (cmax != NO_ELEM && tr == 0) atomicMax(a.flags + 1, p + 1);
         }
