@@ -118,7 +118,7 @@ OZAKI_HD uint64_t fp64_mul_emulated(uint64_t a, uint64_t b) {
     return sign | r;
 }
 
-// n * 2^e2 as FP64 bits for an integer |n| < 2^53 (exact), integer-only; flushed / saturated outside the normal range.
+// n * 2^e2 as FP64 bits for an integer |n| <= 2^53 (exact), integer-only; flushed / saturated outside the normal range.
 OZAKI_HD uint64_t int53_scaled_to_fp64(int64_t n, int e2) {
     if (n == 0) return 0;
     const uint64_t sign = n < 0 ? F64_SIGN : 0;
@@ -127,41 +127,56 @@ OZAKI_HD uint64_t int53_scaled_to_fp64(int64_t n, int e2) {
     const int e = 1023 + top + e2;
     if (e <= 0) return sign;
     if (e >= 2047) return sign | F64_INF;
-    return sign | ((uint64_t)e << 52) | ((a << (52 - top)) & F64_FRAC);
+    const uint64_t sig = top <= 52 ? a << (52 - top) : a >> 1;     // top == 53 only for 2^53 itself
+    return sign | ((uint64_t)e << 52) | (sig & F64_FRAC);
 }
 
-// A running FP64 sum of terms v * 2^e2 (v an integer below 2^52 in magnitude), each addition rounded to nearest even.  As long as the sum
-// and the next term fit together into 53 bits (both below 2^52 in units of the smaller of their two scales) the
-// rounded addition is exact, so the sum is held as a 64-bit integer x * 2^ex and an addition is a shift and an
-// integer add; the first addition that may round turns the sum into FP64 bits once and fp64_add_emulated takes over.
-// Bit for bit the chain of rounded additions, inside the normal range.
+// A running FP64 sum of terms v * 2^e2 (v an integer below 2^52 in magnitude), each addition rounded to nearest even.
+// The sum is held as x * 2^ex with a 64-bit integer |x| <= 2^53: an FP64 value written with an unnormalised
+// significand.  When both operands fit one 64-bit integer in units of the smaller of their two scales (the usual
+// case: the method's terms arrive least significant first, a few bits apart), the addition is an integer addition
+// followed by one rounding of the result to 53 significant bits, ties to even -- what the IEEE addition returns,
+// and nothing at all while the result is short enough to be exact.  Operands further apart go through
+// fp64_add_emulated.  Bit for bit the chain of rounded additions, inside the normal range.
 struct RoundedSum {
-    uint64_t w;         // the sum: the integer x of x * 2^ex (two's complement) while exact, FP64 bits afterwards
-    int ex;             // NOT_EXACT once the sum is held as FP64 bits
-    static constexpr int NOT_EXACT = -0x40000000;
+    int64_t x;
+    int ex;
 
-    OZAKI_HD bool exact() const { return ex != NOT_EXACT; }
-    OZAKI_HD void start_at_zero() { w = 0; ex = 0; }
-    OZAKI_HD void start_at(uint64_t fp64_bits) { w = fp64_bits; ex = NOT_EXACT; }
-    OZAKI_HD void add(int64_t v, int e2) {
-        if (v == 0) return;                                     // adding an exact zero changes nothing
-        if (exact()) {
-            const int64_t x = (int64_t)w;
-            if (x == 0) { w = (uint64_t)v; ex = e2; return; }
-            const int lo = ex < e2 ? ex : e2, sx = ex - lo, sv = e2 - lo;
-            const uint64_t ax = (uint64_t)(x < 0 ? -x : x);
-            const uint64_t av = (uint64_t)(v < 0 ? -v : v);
-            if (64 - clz64(ax) + sx <= 52 && 64 - clz64(av) + sv <= 52) {
-                w = (w << sx) + ((uint64_t)v << sv);
-                ex = lo;
-                return;
-            }
-            w = int53_scaled_to_fp64(x, ex);
-            ex = NOT_EXACT;
-        }
-        w = fp64_add_emulated(w, int53_scaled_to_fp64(v, e2));
+    OZAKI_HD void start_at_zero() { x = 0; ex = 0; }
+    OZAKI_HD void start_at(uint64_t fp64_bits) {
+        const int e = (int)((fp64_bits >> 52) & 0x7FF);
+        const int64_t m = (int64_t)((fp64_bits & F64_FRAC) | F64_HIDDEN);
+        x = e == 0 ? 0 : (fp64_bits & F64_SIGN) ? -m : m;
+        ex = e - 1075;
     }
-    OZAKI_HD uint64_t value() const { return exact() ? int53_scaled_to_fp64((int64_t)w, ex) : w; }
+    // Returns whether the addition was done on integers (false: the general routine was needed).
+    OZAKI_HD bool add(int64_t v, int e2) {
+        if (v == 0) return true;                                // adding an exact zero changes nothing
+        if (x == 0) { x = v; ex = e2; return true; }
+        const int d = e2 - ex;
+        const uint64_t sv = (uint64_t)(v >> 63);
+        const int nv = 64 - clz64(((uint64_t)v ^ sv) - sv);     // significant bits of |v|
+        if (d >= -8 && nv + d <= 62) {                          // |x| << 8 and |v| << d both stay below 2^62
+            const int left_x = d < 0 ? -d : 0, left_v = d < 0 ? 0 : d;
+            const int64_t t = (int64_t)(((uint64_t)x << left_x) + ((uint64_t)v << left_v));
+            const int e = d < 0 ? e2 : ex;
+            const uint64_t st = (uint64_t)(t >> 63);
+            const uint64_t a = ((uint64_t)t ^ st) - st;         // |t|
+            const int drop = 11 - clz64(a | 1);                 // bits beyond 53
+            if (drop > 0) {
+                const uint64_t q = (a + ((1ull << (drop - 1)) - 1) + ((a >> drop) & 1)) >> drop;      // ties to even; may reach 2^53
+                x = (int64_t)((q ^ st) - st);
+                ex = e + drop;
+            } else {
+                x = t;
+                ex = e;
+            }
+            return true;
+        }
+        start_at(fp64_add_emulated(int53_scaled_to_fp64(x, ex), int53_scaled_to_fp64(v, e2)));
+        return false;
+    }
+    OZAKI_HD uint64_t value() const { return int53_scaled_to_fp64(x, ex); }
 };
 
 // A 192-bit two's-complement fixed-point accumulator: the exact sum of terms v * 2^sh units (v an integer of at most

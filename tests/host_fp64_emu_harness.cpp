@@ -16,15 +16,14 @@ void host_int53_scaled_to_fp64(const int64_t* v, const int* e2, uint64_t* out, s
     for (size_t i = 0; i < n; ++i) out[i] = ozaki::int53_scaled_to_fp64(v[i], e2[i]);
 }
 // n_seq sequences of len terms v * 2^e2 each, summed front to back with ozaki::RoundedSum; start[i] != 0 begins
-// from those FP64 bits instead of zero.  exact_adds counts the additions taken in the integer phase.
+// from those FP64 bits instead of zero.  exact_adds counts the additions done on integers.
 void host_rounded_sum(const int64_t* v, const int* e2, const uint64_t* start, uint64_t* out, long long* exact_adds, size_t n_seq, size_t len) {
     long long cnt = 0;
     for (size_t i = 0; i < n_seq; ++i) {
         ozaki::RoundedSum s;
         if (start[i]) s.start_at(start[i]); else s.start_at_zero();
         for (size_t j = 0; j < len; ++j) {
-            s.add(v[i * len + j], e2[i * len + j]);
-            cnt += s.exact();
+            cnt += s.add(v[i * len + j], e2[i * len + j]);
         }
         out[i] = s.value();
     }
