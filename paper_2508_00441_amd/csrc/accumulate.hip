@@ -152,7 +152,7 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
     auto add_run = [&](int r, run_t run_sum, int run_e) {
         if (run_sum == 0) return;                                     // adding an exact zero changes nothing
         if constexpr (HW) Sd[r] = Sd[r] + ldexp((double)run_sum, run_e - a.two_b);
-        if constexpr (EMU) E[r].add((int64_t)run_sum, run_e - a.two_b);
+        if constexpr (EMU) E[r].add(run_sum, run_e - a.two_b);
         if constexpr (EXACT) X[r].add((int64_t)run_sum, EXACT_WINDOW_BITS + run_e);      // unit: 2^(-2b - window) of the leading scale
     };
     // Per element, consecutive stored runs of one anti-diagonal with the same scale are merged further (integer,

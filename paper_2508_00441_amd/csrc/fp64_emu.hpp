@@ -152,10 +152,22 @@ struct RoundedSum {
     // Returns whether the addition was done on integers (false: the general routine was needed).
     OZAKI_HD bool add(int64_t v, int e2) {
         if (v == 0) return true;                                // adding an exact zero changes nothing
+        const uint64_t sv = (uint64_t)(v >> 63);
+        return add_bits(v, e2, 64 - clz64(((uint64_t)v ^ sv) - sv));
+    }
+    OZAKI_HD bool add(int v, int e2) {                          // same for a 32-bit term: cheaper bit count
+        if (v == 0) return true;
+        const uint32_t av = (uint32_t)(v < 0 ? -v : v);
+#if defined(__HIP_DEVICE_COMPILE__)
+        return add_bits((int64_t)v, e2, 32 - __clz((int)av));
+#else
+        return add_bits((int64_t)v, e2, 32 - __builtin_clz(av));
+#endif
+    }
+    // v != 0 with nv significant bits
+    OZAKI_HD bool add_bits(int64_t v, int e2, int nv) {
         if (x == 0) { x = v; ex = e2; return true; }
         const int d = e2 - ex;
-        const uint64_t sv = (uint64_t)(v >> 63);
-        const int nv = 64 - clz64(((uint64_t)v ^ sv) - sv);     // significant bits of |v|
         if (d >= -8 && nv + d <= 62) {                          // |x| << 8 and |v| << d both stay below 2^62
             const int left_x = d < 0 ? -d : 0, left_v = d < 0 ? 0 : d;
             const int64_t t = (int64_t)(((uint64_t)x << left_x) + ((uint64_t)v << left_v));
