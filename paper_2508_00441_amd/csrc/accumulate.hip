@@ -72,6 +72,7 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
     __shared__ int relA[MAX_SLICES][32];
     __shared__ int relB[MAX_SLICES][32];
     __shared__ uint32_t entries[MAX_PAIRS];           // stored runs of this tile: slot | p << 12 | q << 18 | first-of-diagonal << 24
+    __shared__ int32_t linkA[MAX_SLICES], linkB[MAX_SLICES];      // deltas of the 32 rows / 32 columns, per slice
     __shared__ int n_entries;
 
     const int tid = threadIdx.x;
@@ -92,6 +93,9 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
         relA[p][r] = p == 0 ? ca1 : ca - ca1;
         relB[p][r] = p == 0 ? cb1 : cb - cb1;
     }
+    // the deltas that decide where the GEMM kernel ended its runs at this position: fetched once, all at the same time
+    if (tid < a.order.s) linkA[tid] = a.da[(int64_t)tid * (a.rows_pad_a / LINK_ROWS) + m0 / LINK_ROWS];
+    else if (tid >= 64 && tid - 64 < a.order.s) linkB[tid - 64] = a.db[(int64_t)(tid - 64) * (a.rows_pad_b / LINK_ROWS) + n0 / LINK_ROWS];
     __syncthreads();
 
     const int ml = lane & 31;
@@ -125,9 +129,6 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
     // the whole position) to the pair before it inside its group.  Built by the first wave, one anti-diagonal at a time
     // (an anti-diagonal has at most 32 pairs).
     if (tid < 64) {
-        const int64_t ga = a.rows_pad_a / LINK_ROWS, gb = a.rows_pad_b / LINK_ROWS;
-        const int32_t* dA = a.da + m0 / LINK_ROWS;
-        const int32_t* dB = a.db + n0 / LINK_ROWS;
         int count = 0, slot0 = 0;
         for (int g = a.pass.g_hi; g >= a.pass.g_lo; --g) {
             const int len = diag_len(a.order, g);
@@ -136,7 +137,7 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
             if (tid < len) {
                 const int p = diag_first_p(a.order, g) + tid - 1, q = g - p - 2;     // 0-based slice indices
                 const bool first = tid == 0;                                        // first pair of the anti-diagonal: ends every run
-                start = starts_run(a.order, a.allow_chain, dA, ga, dB, gb, tid, p, q);      // stored on its own
+                start = starts_run(a.order, a.allow_chain, linkA, 1, linkB, 1, tid, p, q);      // stored on its own
                 entry = (uint32_t)(slot0 + tid) | ((uint32_t)p << 12) | ((uint32_t)q << 18) | ((uint32_t)first << 24);
             }
             const unsigned long long mask = __ballot(start);
