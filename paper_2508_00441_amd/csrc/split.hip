@@ -21,6 +21,7 @@
 #include <string.h>
 
 #include "layout.hpp"
+#include "slice_element.hpp"
 
 namespace ozaki {
 
@@ -64,6 +65,7 @@ struct SplitArgs {
 };
 
 constexpr int NO_ELEM = -(1 << 30);
+static_assert(NO_ELEM == NO_CANDIDATE, "the two slicers share the reduction");
 
 // Type2 codes of the two values q0 * 2^-b and q1 * 2^-b (|q| <= 2^b), packed low/high.  The hardware FP32 -> FP8
 // (OCP E4M3 on gfx950) and FP32 -> FP16 conversions are exact here because every such value is a normal number of
@@ -266,16 +268,12 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
     // signed 64-bit integer.  |x^(p)| <= 2^(c_p) bounds |T| by 2^(b+F) = 2^60.
     const int F = 60 - a.b;
 
-    // element state (see decode_element)
-    int64_t tv[8 * U];
-    int pk[8 * U];
     bool nonfinite = false;
     int cmax = NO_ELEM;
     const double* src = vX + row * v_ldv + k0;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
+    // the eight FP64 bit patterns of octet u of this thread (zeros beyond the block)
+    auto load_octet = [&](int u, uint64_t (&bits)[8]) {
         const int64_t ke = 8 * ((int64_t)tr + (int64_t)TPR * u);
-        uint64_t bits[8];
         if (v_vec_ok && ke + 8 <= klen) {
             const ulonglong2* v = reinterpret_cast<const ulonglong2*>(src + ke);
 #pragma unroll
@@ -288,6 +286,91 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
 #pragma unroll
             for (int e = 0; e < 8; ++e) bits[e] = (ke + e < klen) ? __double_as_longlong(src[ke + e]) : 0ull;
         }
+    };
+    // Eq. 4: c = max over the vector of ceil(log2 |x_i|); each thread contributes the maximum over its elements
+    // (from the decoded inputs for the first slice, from the remainders afterwards)
+    auto vector_max = [&](int val, int p) -> int {
+#pragma unroll
+        for (int off = 1; off < (TPR < 64 ? TPR : 64); off <<= 1) {
+            const int o = __shfl_xor(val, off, 64);
+            val = o > val ? o : val;
+        }
+        if (WAVES_PER_ROW > 1) {
+            const int wave = threadIdx.x >> 6;
+            if ((threadIdx.x & 63) == 0) red[p & 1][wave] = val;
+            __syncthreads();
+            const int w0 = (wave / WAVES_PER_ROW) * WAVES_PER_ROW;
+#pragma unroll
+            for (int w = 0; w < WAVES_PER_ROW; ++w) {
+                const int o = red[p & 1][w0 + w];
+                val = o > val ? o : val;
+            }
+        }
+        return val;
+    };
+
+    if constexpr (!FP16) {
+        // ---- slices of at most 7 bits: the element step on 32-bit words (slice_element.hpp)
+        const int pos = F - 32, bias = (1 << (pos - 1)) - 1;
+        const uint32_t keep = ~((1u << pos) - 1u);
+        int hi[8 * U], pk[8 * U];
+        uint32_t lo[8 * U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            uint64_t bits[8];
+            load_octet(u, bits);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) decode_narrow(bits[e], F, hi[8 * u + e], lo[8 * u + e], pk[8 * u + e], cmax, nonfinite);
+        }
+        if (nonfinite) atomicOr(a.flags, 1);
+        int unit_prev = 0;
+        for (int p = 0; p < a.s; ++p) {
+            cmax = vector_max(cmax, p);
+            // count-only mode (slicing until the remainder is zero, paragraph before Eq. 4): something is left before
+            // the (p+1)-th slice, so this vector needs at least p + 1 of them
+            if (v_slices == nullptr && cmax != NO_ELEM && tr == 0) atomicMax(a.flags + 1, p + 1);
+            const int c = (cmax == NO_ELEM) ? 0 : cmax;
+            const int unit = c - a.b;                                  // the slice's unit is 2^(c-b)
+            const int step16 = (unit_prev - unit) * 65536;
+            unit_prev = unit;
+            uint8_t* const dst_slice = v_slices + (size_t)((t * a.s + p) * a.chunks) * (size_t)v_rows_pad * ROWB;
+            int kmax = 0, kmin = 0;
+            uint32_t cd_wait = 0;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                int qs[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    qs[e] = slice_narrow(hi[8 * u + e], lo[8 * u + e], pk[8 * u + e], step16, pos, bias, keep, kmax, kmin, cd_wait);
+                const int64_t ke = 8 * ((int64_t)tr + (int64_t)TPR * u);
+                if (ke < padded && v_slices != nullptr) store_codes<FMT>(qs, ke, dst_slice, v_rows_pad, row, a.b);
+            }
+            if (tr == 0 && v_slices != nullptr) v_exps[(t * a.s + p) * v_rows_pad + row] = c;
+            // this thread's candidate for the next exponent
+            bool needs_low;
+            cmax = narrow_candidate(kmax, kmin, unit, F, needs_low);
+            if (needs_low) {                                           // every remainder of this thread is below 2^32 units
+                uint32_t mx = 0;
+#pragma unroll
+                for (int i = 0; i < 8 * U; ++i) {
+                    const uint32_t ar = pk[i] == 0 ? narrow_small_abs(hi[i], lo[i]) : 0u;
+                    mx = ar > mx ? ar : mx;
+                }
+                cmax = narrow_candidate_low(mx, unit, F);
+            }
+            const int cw = (int)cd_wait - CD_BIAS;
+            cmax = (cd_wait != 0 && cw > cmax) ? cw : cmax;
+        }
+        return;
+    }
+
+    // ---- FP16 slices (more than 7 bits wide): element state as described at decode_element
+    int64_t tv[8 * U];
+    int pk[8 * U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        uint64_t bits[8];
+        load_octet(u, bits);
 #pragma unroll
         for (int e = 0; e < 8; ++e) decode_element(bits[e], F, tv[8 * u + e], pk[8 * u + e], cmax, nonfinite);
     }
@@ -295,28 +378,9 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
 
     int c_prev = 0;
     for (int p = 0; p < a.s; ++p) {
-        // ---- Eq. 4: c = max over the vector of ceil(log2 |x_i|); each thread contributes the maximum over its
-        // elements (from the decoded inputs for the first slice, from the remainders afterwards)
-#pragma unroll
-        for (int off = 1; off < (TPR < 64 ? TPR : 64); off <<= 1) {
-            const int o = __shfl_xor(cmax, off, 64);
-            cmax = o > cmax ? o : cmax;
-        }
-        if (WAVES_PER_ROW > 1) {
-            const int wave = threadIdx.x >> 6;
-            if ((threadIdx.x & 63) == 0) red[p & 1][wave] = cmax;
-            __syncthreads();
-            const int w0 = (wave / WAVES_PER_ROW) * WAVES_PER_ROW;
-#pragma unroll
-            for (int w = 0; w < WAVES_PER_ROW; ++w) {
-                const int o = red[p & 1][w0 + w];
-                cmax = o > cmax ? o : cmax;
-            }
-        }
+        cmax = vector_max(cmax, p);
         if (v_slices == nullptr) {
-            // count-only mode (slicing until the remainder is zero, paragraph before Eq. 4): something is left before the (p+1)-th
-            // slice, so this vector needs at least p + 1 of them
-            if (cmax != NO_ELEM && tr == 0) atomicMax(a.flags + 1, p + 1);
+            if (cmax != NO_ELEM && tr == 0) atomicMax(a.flags + 1, p + 1);      // count-only mode
         }
         const int c = (cmax == NO_ELEM) ? 0 : cmax;
         const int unit = c - a.b;                                      // the slice's unit is 2^(c-b)

@@ -330,3 +330,54 @@ def test_contexts_are_created_selected_and_destroyed_on_the_host():
     lib.ozaki_context_destroy(h1)
     assert lib.load().ozaki_context_destroy(None) == -1
     assert lib.load().ozaki_context_create(None) == -1
+
+
+@pytest.fixture(scope="module")
+def host_slicer(tmp_path_factory):
+    out = tmp_path_factory.mktemp("slicer") / "libhostslicer.so"
+    subprocess.check_call(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-o", str(out),
+                           os.path.join(ROOT, "tests", "host_slice_element_harness.cpp")])
+    return ctypes.CDLL(str(out))
+
+
+def _host_slice(lib, x, b, s, chunk):
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    q = np.empty((s, x.size), dtype=np.int32)
+    c = np.empty(s, dtype=np.int32)
+    rc = lib.host_slice_vector_narrow(x.ctypes.data_as(ctypes.c_void_p), ctypes.c_size_t(x.size), b, s, chunk,
+                                      q.ctypes.data_as(ctypes.c_void_p), c.ctypes.data_as(ctypes.c_void_p))
+    return q, c, rc >> 1
+
+
+@pytest.mark.parametrize("b", [2, 3, 4, 6, 7])
+def test_product_narrow_slicer_on_host_equals_oracle(host_slicer, b):
+    """The slicer's 32-bit element step (rounding, remainder, the keys that give the next exponent, waiting elements)
+    against Eq. 4-8 of the oracle: corner-case vectors, wide-range vectors, short integers (every remainder below
+    2^32 units: the keys cannot tell and the lower words decide), several thread sizes."""
+    from oracle import ozaki_oracle as oo
+    from paper_2508_00441_amd import inputs
+    rng = np.random.default_rng(100 + b)
+    rho = 53 - b
+    k = 200
+    X = inputs.nasty_rows(rng, 40, k)
+    extra = [
+        inputs.phi_matrix(6, k, 6.0, rng),                                         # very wide range: long waits
+        rng.integers(-1000, 1001, (4, k)).astype(np.float64),                      # short integers: exhausted early
+        np.ldexp(rng.integers(-(1 << 20), 1 << 20, (4, k)).astype(np.float64), -30) + 3.0,      # tiny remainders after slice 1
+        np.ldexp(1.0, rng.integers(-40, 40, (4, k))) * np.where(rng.random((4, k)) < 0.5, -1, 1),     # powers of two only
+        inputs.phi_matrix(4, k, 1.0, rng) * 2.0 ** -1040,                          # subnormal inputs
+    ]
+    X = np.vstack([X] + extra)
+    X[41, 7] = 0.0
+    s = 16
+    sl, cs, _ = oo.slice_rows(X, rho, s)
+    want_q = np.stack([oo.slice_integers(v, b) for v in sl]).astype(np.int64)      # [s][rows][k]
+    want_c = np.stack(cs)                                                          # [s][rows]
+    low_decisions = 0
+    for r in range(X.shape[0]):
+        for chunk in (1, 16, k):
+            q, c, low = _host_slice(host_slicer, X[r], b, s, chunk)
+            assert np.array_equal(c, want_c[:, r]), (r, chunk, c, want_c[:, r])
+            assert np.array_equal(q, want_q[:, r, :]), (r, chunk)
+            low_decisions += low
+    assert low_decisions > 0                                                       # the fallback of the keys was exercised
