@@ -66,12 +66,13 @@ OZAKI_SLICE_HD void decode_narrow(uint64_t w, int F, int& hi, uint32_t& lo, int&
 }
 
 // One element, one slice.  step16 = (previous unit - this unit) * 65536 (minus this unit for the first slice);
-// pos = F - 32, bias = 2^(pos-1) - 1, keep = ~(2^pos - 1).  Returns q; kmax / kmin collect the signed keys of the
-// remainders, cd_wait the largest lower half of the elements that go on waiting.
+// pos = F - 32, bias = 2^(pos-1) - 1, keep = ~(2^pos - 1).  Returns q * 2^pos (the slice integer where it sits in the
+// upper word); kmax / kmin collect the signed keys of the remainders, cd_wait the largest lower half of the elements
+// that go on waiting.
 OZAKI_SLICE_HD int slice_narrow(int& hi, uint32_t& lo, int& pk, int step16, int pos, int bias, uint32_t keep, int& kmax, int& kmin,
                                 uint32_t& cd_wait) {
     pk += step16;
-    int q = 0;
+    int q_at_pos = 0;
     if (pk >= 0) {
         const int sh = pk >> 16;                                     // 0 .. 60: nothing is shifted out (|T| <= 2^60 afterwards)
         const uint64_t T = (((uint64_t)(uint32_t)hi << 32) | lo) << (sh & 63);
@@ -79,8 +80,8 @@ OZAKI_SLICE_HD int slice_narrow(int& hi, uint32_t& lo, int& pk, int step16, int 
         lo = (uint32_t)T;
         const int nz = lo != 0 ? 1 : 0;
         const int sum = hi + bias + (nz | ((hi >> pos) & 1));
-        q = sum >> pos;
-        hi -= (int)((uint32_t)sum & keep);
+        q_at_pos = (int)((uint32_t)sum & keep);
+        hi -= q_at_pos;
         const int key = (int)(((uint32_t)hi << 1) | (uint32_t)nz);
         kmax = key > kmax ? key : kmax;
         kmin = key < kmin ? key : kmin;
@@ -88,7 +89,7 @@ OZAKI_SLICE_HD int slice_narrow(int& hi, uint32_t& lo, int& pk, int step16, int 
     }
     const uint32_t cdw = (uint32_t)pk & 0xFFFFu;                     // 0 unless the element goes on waiting
     cd_wait = cdw > cd_wait ? cdw : cd_wait;
-    return q;
+    return q_at_pos;
 }
 
 // |T| of a remainder known to be below 2^32 in magnitude (key 0 or 1)

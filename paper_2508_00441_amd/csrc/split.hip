@@ -225,6 +225,28 @@ __device__ __forceinline__ void store_codes(const int (&qs)[8], int64_t ke, uint
     }
 }
 
+// The same for FP8 codes of the eight values qs[e] / scale (integers times a power of two, scale a power of two): the
+// scaled FP32 -> FP8 pair conversion of gfx950 divides by the scale, so the slice integer is converted from where it
+// sits in the slicer's upper word, without a shift or a separate scaling.  Exact for the same reason as above.
+__device__ __forceinline__ void store_fp8_codes_scaled(const int (&qs)[8], float scale, int64_t ke, uint8_t* dst_slice, int64_t v_rows_pad,
+                                                       int64_t row) {
+    typedef short short2v __attribute__((ext_vector_type(2)));
+    uint32_t w[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        short2v r = {0, 0};
+        r = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(r, (float)qs[4 * h], (float)qs[4 * h + 1], scale, false);
+        r = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(r, (float)qs[4 * h + 2], (float)qs[4 * h + 3], scale, true);
+        w[h] = __builtin_bit_cast(uint32_t, r);
+    }
+    const int64_t kc = ke / CHUNK_BYTES;
+    uint8_t* dst = dst_slice + ((size_t)kc * v_rows_pad + row) * CHUNK_BYTES + (ke % CHUNK_BYTES);
+    uint2 v;
+    v.x = w[0];
+    v.y = w[1];
+    *reinterpret_cast<uint2*>(dst) = v;
+}
+
 // smallest c with v * 2^(unit - F) <= 2^c, for v != 0
 __device__ __forceinline__ int ceil_log2_scaled(uint64_t v, int unit, int F) {
     const int L = 64 - __clzll((long long)v);
@@ -313,6 +335,7 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
         // ---- slices of at most 7 bits: the element step on 32-bit words (slice_element.hpp)
         const int pos = F - 32, bias = (1 << (pos - 1)) - 1;
         const uint32_t keep = ~((1u << pos) - 1u);
+        const float code_scale = ldexpf(1.0f, pos + a.b);              // q * 2^pos / code_scale = q * 2^-b, the slice value
         int hi[8 * U], pk[8 * U];
         uint32_t lo[8 * U];
 #pragma unroll
@@ -338,12 +361,18 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
             uint32_t cd_wait = 0;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                int qs[8];
+                int qs[8];                                             // q * 2^pos
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
                     qs[e] = slice_narrow(hi[8 * u + e], lo[8 * u + e], pk[8 * u + e], step16, pos, bias, keep, kmax, kmin, cd_wait);
                 const int64_t ke = 8 * ((int64_t)tr + (int64_t)TPR * u);
-                if (ke < padded && v_slices != nullptr) store_codes<FMT>(qs, ke, dst_slice, v_rows_pad, row, a.b);
+                if constexpr (FMT == FMT_FP8) {
+                    if (ke < padded && v_slices != nullptr) store_fp8_codes_scaled(qs, code_scale, ke, dst_slice, v_rows_pad, row);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) qs[e] >>= pos;
+                    if (ke < padded && v_slices != nullptr) store_codes<FMT>(qs, ke, dst_slice, v_rows_pad, row, a.b);
+                }
             }
             if (tr == 0 && v_slices != nullptr) v_exps[(t * a.s + p) * v_rows_pad + row] = c;
             // this thread's candidate for the next exponent

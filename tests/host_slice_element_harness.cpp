@@ -30,7 +30,7 @@ int host_slice_vector_narrow(const uint64_t* x, size_t n, int b, int s, int chun
             int kmax = 0, kmin = 0;
             uint32_t cd_wait = 0;
             for (size_t i = i0; i < i1; ++i)
-                q_out[(size_t)p * n + i] = slice_narrow(hi[i], lo[i], pk[i], step16, pos, bias, keep, kmax, kmin, cd_wait);
+                q_out[(size_t)p * n + i] = slice_narrow(hi[i], lo[i], pk[i], step16, pos, bias, keep, kmax, kmin, cd_wait) >> pos;
             bool needs_low;
             int cand = narrow_candidate(kmax, kmin, unit, F, needs_low);
             if (needs_low) {
