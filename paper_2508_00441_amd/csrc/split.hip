@@ -253,8 +253,24 @@ __device__ __forceinline__ int ceil_log2_scaled(uint64_t v, int unit, int F) {
     return unit - F + L - (((v & (v - 1)) == 0) ? 1 : 0);
 }
 
+// Maximum over the 64 lanes of a wave, returned to all of them: data-parallel-primitive steps inside rows of 16 lanes
+// (swap inside pairs, pairs inside quads, mirror the half rows, mirror the rows), then the last lane of a row is
+// passed on to the next row(s), and lane 63 holds the maximum.
+__device__ __forceinline__ int wave_max(int v) {
+    auto step = [](int x, int y) { return y > x ? y : x; };
+    v = step(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false));      // quad_perm [1,0,3,2]
+    v = step(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false));      // quad_perm [2,3,0,1]
+    v = step(v, __builtin_amdgcn_update_dpp(v, v, 0x141, 0xF, 0xF, false));     // row_half_mirror
+    v = step(v, __builtin_amdgcn_update_dpp(v, v, 0x140, 0xF, 0xF, false));     // row_mirror
+    v = step(v, __builtin_amdgcn_update_dpp(v, v, 0x142, 0xA, 0xF, false));     // row_bcast15 into rows 1 and 3
+    v = step(v, __builtin_amdgcn_update_dpp(v, v, 0x143, 0xC, 0xF, false));     // row_bcast31 into rows 2 and 3
+    return __builtin_amdgcn_readlane(v, 63);
+}
+
+// (At least four waves per SIMD, i.e. at most 128 registers: two 512-thread workgroups per CU, so that one computes while
+// the other waits at its barrier.)
 template <int U, int TPR, int FMT>
-__global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArgs a) {
+__global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) __attribute__((amdgpu_waves_per_eu(4))) split_kernel(SplitArgs a) {
     constexpr bool FP16 = FMT == FMT_FP16;
     constexpr bool FP6 = fmt_is_fp6(FMT);
     constexpr int BLOCK = TPR < 256 ? 256 : TPR;
@@ -312,11 +328,8 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
     // Eq. 4: c = max over the vector of ceil(log2 |x_i|); each thread contributes the maximum over its elements
     // (from the decoded inputs for the first slice, from the remainders afterwards)
     auto vector_max = [&](int val, int p) -> int {
-#pragma unroll
-        for (int off = 1; off < (TPR < 64 ? TPR : 64); off <<= 1) {
-            const int o = __shfl_xor(val, off, 64);
-            val = o > val ? o : val;
-        }
+        static_assert(TPR >= 64, "a wave never holds parts of two vectors");
+        val = wave_max(val);
         if (WAVES_PER_ROW > 1) {
             const int wave = threadIdx.x >> 6;
             if ((threadIdx.x & 63) == 0) red[p & 1][wave] = val;
@@ -336,59 +349,88 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) split_kernel(SplitArg
         const int pos = F - 32, bias = (1 << (pos - 1)) - 1;
         const uint32_t keep = ~((1u << pos) - 1u);
         const float code_scale = ldexpf(1.0f, pos + a.b);              // q * 2^pos / code_scale = q * 2^-b, the slice value
-        int hi[8 * U], pk[8 * U];
-        uint32_t lo[8 * U];
+        uint64_t T[8 * U];                                             // element state, see slice_element.hpp
+        int pk[8 * U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             uint64_t bits[8];
             load_octet(u, bits);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) decode_narrow(bits[e], F, hi[8 * u + e], lo[8 * u + e], pk[8 * u + e], cmax, nonfinite);
+            for (int e = 0; e < 8; ++e) decode_narrow(bits[e], F, T[8 * u + e], pk[8 * u + e], cmax, nonfinite);
         }
         if (nonfinite) atomicOr(a.flags, 1);
-        int unit_prev = 0;
-        for (int p = 0; p < a.s; ++p) {
+        int unit_prev = 0, unit = 0, c = 0, step = 0;
+        uint8_t* dst_slice = nullptr;
+        int kmax, kmin;
+        uint32_t cd_wait;
+        // head of slice p: Eq. 4, the unit 2^(c-b) and the distance from the previous unit
+        auto begin_slice = [&](int p) {
             cmax = vector_max(cmax, p);
             // count-only mode (slicing until the remainder is zero, paragraph before Eq. 4): something is left before
             // the (p+1)-th slice, so this vector needs at least p + 1 of them
             if (v_slices == nullptr && cmax != NO_ELEM && tr == 0) atomicMax(a.flags + 1, p + 1);
-            const int c = (cmax == NO_ELEM) ? 0 : cmax;
-            const int unit = c - a.b;                                  // the slice's unit is 2^(c-b)
-            const int step16 = (unit_prev - unit) * 65536;
+            c = (cmax == NO_ELEM) ? 0 : cmax;
+            unit = c - a.b;
+            step = unit_prev - unit;
             unit_prev = unit;
-            uint8_t* const dst_slice = v_slices + (size_t)((t * a.s + p) * a.chunks) * (size_t)v_rows_pad * ROWB;
-            int kmax = 0, kmin = 0;
-            uint32_t cd_wait = 0;
+            dst_slice = v_slices + (size_t)((t * a.s + p) * a.chunks) * (size_t)v_rows_pad * ROWB;
+            kmax = KEY_NONE_MAX;
+            kmin = KEY_NONE_MIN;
+            cd_wait = 0;
+        };
+        auto store_octet = [&](int u, int (&qs)[8]) {                   // qs: q * 2^pos
+            const int64_t ke = 8 * ((int64_t)tr + (int64_t)TPR * u);
+            if constexpr (FMT == FMT_FP8) {
+                if (ke < padded && v_slices != nullptr) store_fp8_codes_scaled(qs, code_scale, ke, dst_slice, v_rows_pad, row);
+            } else {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                int qs[8];                                             // q * 2^pos
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    qs[e] = slice_narrow(hi[8 * u + e], lo[8 * u + e], pk[8 * u + e], step16, pos, bias, keep, kmax, kmin, cd_wait);
-                const int64_t ke = 8 * ((int64_t)tr + (int64_t)TPR * u);
-                if constexpr (FMT == FMT_FP8) {
-                    if (ke < padded && v_slices != nullptr) store_fp8_codes_scaled(qs, code_scale, ke, dst_slice, v_rows_pad, row);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) qs[e] >>= pos;
-                    if (ke < padded && v_slices != nullptr) store_codes<FMT>(qs, ke, dst_slice, v_rows_pad, row, a.b);
-                }
+                for (int e = 0; e < 8; ++e) qs[e] >>= pos;
+                if (ke < padded && v_slices != nullptr) store_codes<FMT>(qs, ke, dst_slice, v_rows_pad, row, a.b);
             }
+        };
+        // tail of slice p: the exponent goes out, the thread forms its candidate for the next one
+        auto end_slice = [&](int p, bool settled) {
             if (tr == 0 && v_slices != nullptr) v_exps[(t * a.s + p) * v_rows_pad + row] = c;
-            // this thread's candidate for the next exponent
-            bool needs_low;
-            cmax = narrow_candidate(kmax, kmin, unit, F, needs_low);
-            if (needs_low) {                                           // every remainder of this thread is below 2^32 units
-                uint32_t mx = 0;
+            bool needs_exact;
+            cmax = narrow_candidate(kmax, kmin, unit, F, needs_exact);
+            if (needs_exact) {                                         // the upper words cannot tell: all 64 bits of the remainders
+                uint64_t mx = 0;
 #pragma unroll
                 for (int i = 0; i < 8 * U; ++i) {
-                    const uint32_t ar = pk[i] == 0 ? narrow_small_abs(hi[i], lo[i]) : 0u;
+                    const uint64_t ar = (settled || pk[i] == 0) ? narrow_abs(T[i]) : 0ull;
                     mx = ar > mx ? ar : mx;
                 }
-                cmax = narrow_candidate_low(mx, unit, F);
+                cmax = narrow_candidate_exact(mx, unit, F);
             }
             const int cw = (int)cd_wait - CD_BIAS;
             cmax = (cd_wait != 0 && cw > cmax) ? cw : cmax;
+        };
+        // first the slices during which some element of this wave still waits ...
+        int p = 0;
+        for (bool settled = false; p < a.s && !settled; ++p) {
+            begin_slice(p);
+            const int step16 = step * 65536;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                int qs[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) qs[e] = slice_narrow(T[8 * u + e], pk[8 * u + e], step16, pos, bias, keep, kmax, kmin, cd_wait);
+                store_octet(u, qs);
+            }
+            settled = __ballot(cd_wait != 0) == 0ull;
+            end_slice(p, false);
+        }
+        // ... then the rest: every element is in fixed-point form, one shift for all, no control words
+        for (; p < a.s; ++p) {
+            begin_slice(p);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                int qs[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) qs[e] = slice_narrow_active(T[8 * u + e], step, pos, bias, keep, kmax, kmin);
+                store_octet(u, qs);
+            }
+            end_slice(p, true);
         }
         return;
     }
