@@ -136,8 +136,10 @@ OZAKI_HD uint64_t int53_scaled_to_fp64(int64_t n, int e2) {
 // significand.  When both operands fit one 64-bit integer in units of the smaller of their two scales (the usual
 // case: the method's terms arrive least significant first, a few bits apart), the addition is an integer addition
 // followed by one rounding of the result to 53 significant bits, ties to even -- what the IEEE addition returns,
-// and nothing at all while the result is short enough to be exact.  Operands further apart go through
-// fp64_add_emulated.  Bit for bit the chain of rounded additions, inside the normal range.
+// and nothing at all while the result is short enough to be exact.  A term that towers over the sum is handled the same
+// way after the sum has been cut down to the term's scale with a sticky bit; only a term far below the sum's unit (the
+// method does not produce one) goes through fp64_add_emulated.  Bit for bit the chain of rounded additions, inside the
+// normal range.
 struct RoundedSum {
     int64_t x;
     int ex;
@@ -168,25 +170,42 @@ struct RoundedSum {
     OZAKI_HD bool add_bits(int64_t v, int e2, int nv) {
         if (x == 0) { x = v; ex = e2; return true; }
         const int d = e2 - ex;
-        if (d >= -8 && nv + d <= 62) {                          // |x| << 8 and |v| << d both stay below 2^62
-            const int left_x = d < 0 ? -d : 0, left_v = d < 0 ? 0 : d;
-            const int64_t t = (int64_t)(((uint64_t)x << left_x) + ((uint64_t)v << left_v));
-            const int e = d < 0 ? e2 : ex;
-            const uint64_t st = (uint64_t)(t >> 63);
-            const uint64_t a = ((uint64_t)t ^ st) - st;         // |t|
-            const int drop = 11 - clz64(a | 1);                 // bits beyond 53
-            if (drop > 0) {
-                const uint64_t q = (a + ((1ull << (drop - 1)) - 1) + ((a >> drop) & 1)) >> drop;      // ties to even; may reach 2^53
-                x = (int64_t)((q ^ st) - st);
-                ex = e + drop;
-            } else {
-                x = t;
-                ex = e;
-            }
-            return true;
+        if (d < -8) {                                           // the term lies far below the sum's unit: general routine
+            start_at(fp64_add_emulated(int53_scaled_to_fp64(x, ex), int53_scaled_to_fp64(v, e2)));
+            return false;
         }
-        start_at(fp64_add_emulated(int53_scaled_to_fp64(x, ex), int53_scaled_to_fp64(v, e2)));
-        return false;
+        int64_t t;
+        int e;
+        if (nv + d <= 62) {                                     // |x| << 8 and |v| << d both stay below 2^62
+            const int left_x = d < 0 ? -d : 0, left_v = d < 0 ? 0 : d;
+            t = (int64_t)(((uint64_t)x << left_x) + ((uint64_t)v << left_v));
+            e = d < 0 ? e2 : ex;
+        } else {
+            // The term towers over the sum: bring the term's leading bit to position 61 and the sum down to that unit,
+            // by r >= 1 bits; what the sum loses is kept as a set lowest bit.  The result then has at least 60 bits,
+            // at least 7 are dropped, and an odd integer is never a tie or a 53-bit number at that cut, so the
+            // rounding below sees the same side of every boundary as the exact sum does.
+            const int up = 62 - nv, r = d - up;                 // r = nv + d - 62 > 0
+            const uint64_t sx = (uint64_t)(x >> 63);
+            const uint64_t ax = ((uint64_t)x ^ sx) - sx;
+            const uint64_t kept = r < 64 ? ax >> r : 0;
+            const uint64_t lost = r < 64 ? ax & ((1ull << r) - 1) : ax;
+            const uint64_t xs = kept | (lost != 0 ? 1u : 0u);
+            t = (int64_t)(((uint64_t)v << up) + ((xs ^ sx) - sx));
+            e = e2 - up;
+        }
+        const uint64_t st = (uint64_t)(t >> 63);
+        const uint64_t a = ((uint64_t)t ^ st) - st;             // |t|
+        const int drop = 11 - clz64(a | 1);                     // bits beyond 53
+        if (drop > 0) {
+            const uint64_t q = (a + ((1ull << (drop - 1)) - 1) + ((a >> drop) & 1)) >> drop;      // ties to even; may reach 2^53
+            x = (int64_t)((q ^ st) - st);
+            ex = e + drop;
+        } else {
+            x = t;
+            ex = e;
+        }
+        return true;
     }
     OZAKI_HD uint64_t value() const { return int53_scaled_to_fp64(x, ex); }
 };
