@@ -247,6 +247,45 @@ __device__ __forceinline__ void store_fp8_codes_scaled(const int (&qs)[8], float
     *reinterpret_cast<uint2*>(dst) = v;
 }
 
+// Where the eight 6-bit codes of one octet of a vector go inside a slice matrix: a 32-bit and a 16-bit store (see
+// store_codes).  The same for every slice, so a thread works it out once per octet.
+struct Fp6Slot {
+    size_t at32, at16;     // byte offsets from the slice matrix
+    bool low32;            // the 32-bit store takes bits 0..31 of the 48 (else bits 16..47)
+};
+__device__ __forceinline__ Fp6Slot fp6_slot(int64_t ke, int64_t v_rows_pad, int64_t row) {
+    const int64_t kc = ke / CHUNK_BYTES;
+    const int o = (int)((ke % CHUNK_BYTES) / 8), g = o >> 2, j = o & 3;
+    const size_t chunk = (size_t)kc * v_rows_pad * CHUNK_BYTES_FP6;
+    const size_t p16 = chunk + ((size_t)g * v_rows_pad + row) * 16;
+    const size_t p8 = chunk + (size_t)v_rows_pad * 32 + ((size_t)g * v_rows_pad + row) * 8;
+    Fp6Slot s;
+    s.at32 = j == 0 ? p16 : j == 1 ? p16 + 8 : j == 2 ? p16 + 12 : p8 + 4;
+    s.at16 = j == 0 ? p16 + 4 : j == 1 ? p16 + 6 : j == 2 ? p8 : p8 + 2;
+    s.low32 = (j & 1) == 0;
+    return s;
+}
+// FP6 codes of the eight slice integers given as q * 2^pos (the slicer's upper word), stored at a precomputed slot.
+// The code of the magnitude |q| 2^(K-b) (K = 4 for E2M3, 3 for E3M2) is the magnitude itself for E2M3 and a table
+// entry for E3M2 (see encode_e2m3 / encode_e3m2); bit 5 is the sign.
+template <int FMT>
+__device__ __forceinline__ void store_fp6_codes_at_pos(const int (&qs)[8], int pos, int b, const Fp6Slot& slot, uint8_t* dst_slice) {
+    constexpr int K = FMT == FMT_FP6_E3M2 ? 3 : 4;
+    const int down = pos - (K - b);
+    uint32_t c[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int x = qs[e];
+        const uint32_t mag = (uint32_t)(x < 0 ? -x : x) >> down;
+        const uint32_t sign = ((uint32_t)x >> 26) & 32u;
+        c[e] = (FMT == FMT_FP6_E3M2 ? (uint32_t)((0xCBA986420ull >> (4 * mag)) & 0xFull) : mag) | sign;
+    }
+    const uint32_t lo32 = c[0] | (c[1] << 6) | (c[2] << 12) | (c[3] << 18) | (c[4] << 24) | (c[5] << 30);
+    const uint32_t hi16 = (c[5] >> 2) | (c[6] << 4) | (c[7] << 10);
+    *reinterpret_cast<uint32_t*>(dst_slice + slot.at32) = slot.low32 ? lo32 : (lo32 >> 16) | (hi16 << 16);
+    *reinterpret_cast<uint16_t*>(dst_slice + slot.at16) = (uint16_t)(slot.low32 ? hi16 : lo32);
+}
+
 // smallest c with v * 2^(unit - F) <= 2^c, for v != 0
 __device__ __forceinline__ int ceil_log2_scaled(uint64_t v, int unit, int F) {
     const int L = 64 - __clzll((long long)v);
@@ -349,6 +388,11 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) __attribute__((amdgpu
         const int pos = F - 32, bias = (1 << (pos - 1)) - 1;
         const uint32_t keep = ~((1u << pos) - 1u);
         const float code_scale = ldexpf(1.0f, pos + a.b);              // q * 2^pos / code_scale = q * 2^-b, the slice value
+        Fp6Slot slots[FP6 ? U : 1];                                    // FP6 only: where each octet's codes go inside a slice matrix
+        if constexpr (FP6) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) slots[u] = fp6_slot(8 * ((int64_t)tr + (int64_t)TPR * u), v_rows_pad, row);
+        }
         uint64_t T[8 * U];                                             // element state, see slice_element.hpp
         int pk[8 * U];
 #pragma unroll
@@ -382,6 +426,8 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) __attribute__((amdgpu
             const int64_t ke = 8 * ((int64_t)tr + (int64_t)TPR * u);
             if constexpr (FMT == FMT_FP8) {
                 if (ke < padded && v_slices != nullptr) store_fp8_codes_scaled(qs, code_scale, ke, dst_slice, v_rows_pad, row);
+            } else if constexpr (FP6) {
+                if (ke < padded && v_slices != nullptr) store_fp6_codes_at_pos<FMT>(qs, pos, a.b, slots[u], dst_slice);
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) qs[e] >>= pos;
