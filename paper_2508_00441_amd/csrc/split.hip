@@ -14,7 +14,9 @@
 // q is its rounding to an integer, the remainder is what is left, and moving to the next slice is a left shift
 // by c_p - c_(p+1).  Until then the element waits with its significand and exponent: with b <= 7 it is then smaller
 // than half the unit (q = 0); with wider slices it can already reach the unit, and is rounded in its integer form.
-// No FP64 instruction is executed.
+// No FP64 instruction is executed.  Two forms of this element step: slices of at most 7 bits (FP8, FP6, INT8) work on
+// the upper 32-bit word of the fixed-point number (slice_element.hpp); FP16 slices, whose fixed-point form has fewer
+// than 53 fraction bits, keep the 64-bit step below (decode_element, slice_element).
 //
 // A vector is held in the registers of TPR threads (8*U consecutive elements per thread in U groups of
 // eight) for all s slices, so HBM sees each input element once and each slice code once.
@@ -121,43 +123,38 @@ __device__ __forceinline__ void decode_element(uint64_t w, int F, int64_t& tv, i
     cmax = (mm != 0 && cd > cmax) ? cd : cmax;
 }
 
-// Eq. 5-8 for one element and one slice whose unit is 2^unit: returns q, leaves the exact remainder in (T, st), and
-// keeps track of the largest remainder of the active elements (rmax, in units of 2^(unit - F)) and of the largest
-// ceil(log2 |x|) of the still dormant ones (cdorm).  rescale: left shift that brings an active remainder from the
-// previous slice's unit to this one.  WIDE: the format has slices of more than 7 bits (FP16 only).
-template <bool WIDE>
+// Eq. 5-8 for one element of an FP16 slicing and one slice whose unit is 2^unit: returns q, leaves the exact remainder
+// in (T, st), and keeps track of the largest remainder of the active elements (rmax, in units of 2^(unit - F)) and of
+// the largest ceil(log2 |x|) of the still dormant ones (cdorm).  rescale: left shift that brings an active remainder
+// from the previous slice's unit to this one.  (Slices of at most 7 bits use slice_element.hpp instead.)
 __device__ __forceinline__ int slice_element(int64_t& tv, int& pk, int unit, int rescale, int F, int64_t round_bias, uint64_t& rmax,
                                              int& cdorm) {
     // The bookkeeping of dormant elements is done with selects, the 64-bit arithmetic of active ones behind ONE
     // divergent branch: dormant elements (most of a wide-range vector during its first slices) and zeros skip it.
-    // (A select-only form runs the arithmetic for every element: 2.9 instead of 2.0 ms for two 8192 x 8192 operands;
-    // nested branches cost more scalar instructions than the selects.)
     const int st = pk;
     const bool was_active = st == ACTIVE;
     const int ef = (int)(short)(st & 0xFFFF);
     const bool wakes = !was_active && unit <= ef;          // representable from now on: x / 2^unit * 2^F
     const bool active = was_active || wakes;
-    if constexpr (WIDE) {
-        if (!active && unit - ef + F <= 53) {
-            // Wide slices only (b >= 8, fewer than 53 fraction bits): the element reaches the unit but its
-            // low bits do not fit the fixed-point form yet.  Round its integer form tv * 2^E directly, by
-            // sh = unit - E bits, and let the remainder wait on as a dormant element with the same E.
-            int64_t T = tv;
-            const int sh = unit - ef + F;                  // F < sh <= 53
-            const int64_t q64 = (T + (((int64_t)1 << (sh - 1)) - 1) + ((T >> sh) & 1)) >> sh;
-            T -= q64 << sh;
-            tv = T;
-            const uint64_t ar = (uint64_t)(T < 0 ? -T : T);
-            if (ar == 0) {
-                pk = ACTIVE;                               // nothing left: an active zero
-            } else {
-                const int L = 64 - __clzll((long long)ar);
-                const int cd = ef - F + L - (((ar & (ar - 1)) == 0) ? 1 : 0);
-                pk = (st & 0xFFFF) | (cd << 16);
-                cdorm = cd > cdorm ? cd : cdorm;
-            }
-            return (int)q64;
+    if (!active && unit - ef + F <= 53) {
+        // With b >= 8 there are fewer than 53 fraction bits: the element reaches the unit but its low bits do not
+        // fit the fixed-point form yet.  Round its integer form tv * 2^E directly, by sh = unit - E bits, and let the
+        // remainder wait on as a dormant element with the same E.
+        int64_t T = tv;
+        const int sh = unit - ef + F;                      // F < sh <= 53
+        const int64_t q64 = (T + (((int64_t)1 << (sh - 1)) - 1) + ((T >> sh) & 1)) >> sh;
+        T -= q64 << sh;
+        tv = T;
+        const uint64_t ar = (uint64_t)(T < 0 ? -T : T);
+        if (ar == 0) {
+            pk = ACTIVE;                                   // nothing left: an active zero
+        } else {
+            const int L = 64 - __clzll((long long)ar);
+            const int cd = ef - F + L - (((ar & (ar - 1)) == 0) ? 1 : 0);
+            pk = (st & 0xFFFF) | (cd << 16);
+            cdorm = cd > cdorm ? cd : cdorm;
         }
+        return (int)q64;
     }
     const int cd = st >> 16;
     cdorm = (!active && cd > cdorm) ? cd : cdorm;          // still dormant: |x| < 2^(unit-1), q = 0, remainder = x
@@ -516,7 +513,7 @@ __global__ void __launch_bounds__((TPR < 256 ? 256 : TPR)) __attribute__((amdgpu
         for (int u = 0; u < U; ++u) {
             int qs[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) qs[e] = slice_element<FP16>(tv[8 * u + e], pk[8 * u + e], unit, rescale, F, round_bias, rmax, cdorm);
+            for (int e = 0; e < 8; ++e) qs[e] = slice_element(tv[8 * u + e], pk[8 * u + e], unit, rescale, F, round_bias, rmax, cdorm);
             const int64_t ke = 8 * ((int64_t)tr + (int64_t)TPR * u);
             if (ke < padded && v_slices != nullptr) store_codes<FMT>(qs, ke, dst_slice, v_rows_pad, row, a.b);
         }
@@ -587,6 +584,68 @@ __global__ void __launch_bounds__(1024) split_stream_kernel(SplitArgs a, int64_t
     bool nonfinite = false;
     int cmax = NO_ELEM;
     const double* src = v.X + row * v.ldv + k0;
+    if constexpr (!FP16) {
+        // ---- slices of at most 7 bits: the 32-bit element step of slice_element.hpp, state = (T, control word)
+        uint64_t* const Ts = reinterpret_cast<uint64_t*>(tv);
+        const int pos = F - 32, bias = (1 << (pos - 1)) - 1;
+        const uint32_t keep = ~((1u << pos) - 1u);
+        for (int64_t o = tid; o < n_oct; o += 1024) {
+            const int64_t ke = 8 * o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint64_t w = (ke + e < klen) ? (uint64_t)__double_as_longlong(src[ke + e]) : 0ull;
+                uint64_t T0;
+                int st;
+                decode_narrow(w, F, T0, st, cmax, nonfinite);
+                Ts[ke + e] = T0;
+                pk[ke + e] = st;
+            }
+        }
+        if (nonfinite) atomicOr(a.flags, 1);
+        cmax = block_max(cmax);
+        int unit_prev = 0;
+        for (int p = 0; p < a.s; ++p) {
+            if (v.slices == nullptr && cmax != NO_ELEM && tid == 0) atomicMax(a.flags + 1, p + 1);     // count-only mode
+            const int c = (cmax == NO_ELEM) ? 0 : cmax;
+            const int unit = c - a.b;
+            const int step16 = (unit_prev - unit) * 65536;
+            unit_prev = unit;
+            uint8_t* const dst_slice = v.slices + (size_t)((t * a.s + p) * a.chunks) * (size_t)v.rows_pad * ROWB;
+            int kmax = KEY_NONE_MAX, kmin = KEY_NONE_MIN;
+            uint32_t cd_wait = 0;
+            for (int64_t o = tid; o < n_oct; o += 1024) {
+                const int64_t ke = 8 * o;
+                int qs[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    uint64_t T0 = Ts[ke + e];
+                    int st = pk[ke + e];
+                    qs[e] = slice_narrow(T0, st, step16, pos, bias, keep, kmax, kmin, cd_wait) >> pos;
+                    Ts[ke + e] = T0;
+                    pk[ke + e] = st;
+                }
+                if (v.slices != nullptr) store_codes<FMT>(qs, ke, dst_slice, v.rows_pad, row, a.b);
+            }
+            if (tid == 0 && v.slices != nullptr) v.exps[(t * a.s + p) * v.rows_pad + row] = c;
+            bool needs_exact;
+            cmax = narrow_candidate(kmax, kmin, unit, F, needs_exact);
+            if (needs_exact) {                                         // the upper words cannot tell: once more through the state
+                uint64_t mx = 0;
+                for (int64_t o = tid; o < n_oct; o += 1024)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const uint64_t ar = pk[8 * o + e] == 0 ? narrow_abs(Ts[8 * o + e]) : 0ull;
+                        mx = ar > mx ? ar : mx;
+                    }
+                cmax = narrow_candidate_exact(mx, unit, F);
+            }
+            const int cw = (int)cd_wait - CD_BIAS;
+            cmax = (cd_wait != 0 && cw > cmax) ? cw : cmax;
+            cmax = block_max(cmax);
+        }
+        return;
+    }
+    // ---- FP16 slices: the 64-bit element step (decode_element / slice_element)
     for (int64_t o = tid; o < n_oct; o += 1024) {
         const int64_t ke = 8 * o;
 #pragma unroll
@@ -621,7 +680,7 @@ __global__ void __launch_bounds__(1024) split_stream_kernel(SplitArgs a, int64_t
             for (int e = 0; e < 8; ++e) {
                 int64_t T0 = tv[ke + e];
                 int st = pk[ke + e];
-                qs[e] = slice_element<FP16>(T0, st, unit, rescale, F, round_bias, rmax, cdorm);
+                qs[e] = slice_element(T0, st, unit, rescale, F, round_bias, rmax, cdorm);
                 tv[ke + e] = T0;
                 pk[ke + e] = st;
             }

@@ -488,6 +488,25 @@ def test_all_pairs_mode_matches_oracle(fmt, m, n, k, k_block, s, phi, accum):
         ws.close()
 
 
+@pytest.mark.parametrize("fmt,m,n,k,k_block,s", [("fp8", 130, 90, 1024, 0, 11), ("fp6", 64, 70, 2048, 0, 11), ("int8", 130, 90, 1024, 0, 8),
+                                                  ("fp16", 66, 130, 2048, 1024, 7)])
+@pytest.mark.parametrize("accum", ["hw", "emu", "exact"])
+def test_uniform_1_10_inputs_with_all_pairs_match_oracle(fmt, m, n, k, k_block, s, accum):
+    """The paper's own workload (Section 5.1): entries uniform in (1, 10), every slice pair.  All first slices are
+    positive, so the leading products are k times larger than a random-sign sum and tower over the sum of the less
+    significant anti-diagonals: the case in which the integer-only running sum has to cut the sum down to the term's
+    scale instead of bringing the term to the sum's."""
+    rng = np.random.default_rng(m + n)
+    A, B = inputs.uniform_1_10(m, k, rng), inputs.uniform_1_10(k, n, rng)
+    Ad, Bd = _upload(A, B)
+    C = _run_dgemm(m, n, k, Ad, Bd, fmt, s, k_block, accum, mode="full").T
+    Cref = oz.ozaki_dgemm(A, B, fmt, s, k_block, mode="full", accumulate="exact" if accum == "exact" else "runs")
+    assert np.array_equal(_bits(C), _bits(Cref))
+    ent = [(i, j) for i in range(0, m, 7) for j in range(0, n, 5)]
+    e_ab = exact.sampled_errors_fast(A, B, ent, [C[i, j] for i, j in ent])[0]
+    assert e_ab <= 4 * k * 2.0 ** -53
+
+
 def test_chunked_workspace_gives_identical_bits():
     """The smallest workspace processes the pairs in several passes with the block sum kept in work memory between
     them (one FP64 word per element, three words in the exact mode): same bits as with everything resident."""
