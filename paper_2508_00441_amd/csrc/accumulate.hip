@@ -105,7 +105,7 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
 
     // the block sum of this thread's four elements, in the representation of the mode
     double Sd[4];                                     // HW
-    RoundedSum E[4];                                  // EMU: integer while no rounding can occur, FP64 bits afterwards
+    RoundedSum E[4];                                  // EMU: x * 2^ex with an integer significand of at most 53 bits
     Fixed192 X[4];                                    // EXACT
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -184,15 +184,27 @@ __global__ void __launch_bounds__(256) accumulate_kernel(const AccArgs a) {
         const uint32_t entry = entries[i < n_runs ? i : n_runs - 1];
         return *reinterpret_cast<const uint4*>(a.P + (size_t)(entry & 0xFFFu) * pair_stride + tile_off);
     };
-    // four loads in flight per thread
+    // four loads in flight per thread; the loop is unrolled by four so that each load keeps its registers
     if (n_runs > 0) {
         uint4 v0 = load_run(0), v1 = load_run(1), v2 = load_run(2), v3 = load_run(3);
-        for (int i = 0; i < n_runs; ++i) {
-            const uint4 w = v0;
-            v0 = v1; v1 = v2; v2 = v3;
-            v3 = load_run(i + 4);
-            process(entries[i], w);
+        int i = 0;
+        for (; i + 4 <= n_runs; i += 4) {
+            const uint4 w0 = v0;
+            v0 = load_run(i + 4);
+            process(entries[i], w0);
+            const uint4 w1 = v1;
+            v1 = load_run(i + 5);
+            process(entries[i + 1], w1);
+            const uint4 w2 = v2;
+            v2 = load_run(i + 6);
+            process(entries[i + 2], w2);
+            const uint4 w3 = v3;
+            v3 = load_run(i + 7);
+            process(entries[i + 3], w3);
         }
+        if (i < n_runs) process(entries[i], v0);
+        if (i + 1 < n_runs) process(entries[i + 1], v1);
+        if (i + 2 < n_runs) process(entries[i + 2], v2);
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) add_run(r, run_sum[r], run_e[r]);

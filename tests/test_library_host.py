@@ -245,7 +245,7 @@ def test_product_rounded_sum_on_host_equals_chain_of_fpu_additions(host_emu):
     third = n_seq // 3
     e2[:third] = -100 + np.cumsum(rng.integers(3, 7, (third, length)), axis=1)                 # ascending, like anti-diagonals
     e2[third:2 * third] = rng.integers(-60, 60, (third, length))                              # unordered
-    e2[2 * third:] = rng.integers(-3, 4, (n_seq - 2 * third, length))                         # close: long integer phases
+    e2[2 * third:] = rng.integers(-3, 4, (n_seq - 2 * third, length))                         # close: long stretches without any rounding
     v[2 * third:2 * third + 2000, 1] = -v[2 * third:2 * third + 2000, 0]                      # exact cancellation ...
     e2[2 * third:2 * third + 2000, 1] = e2[2 * third:2 * third + 2000, 0]                     # ... back to zero
     # a sum that rounds up to a power of two (2^54 - 1 -> 2^54: the integer significand reaches 2^53) and goes on
