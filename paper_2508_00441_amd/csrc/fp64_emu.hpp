@@ -168,18 +168,21 @@ struct RoundedSum {
     }
     // v != 0 with nv significant bits
     OZAKI_HD bool add_bits(int64_t v, int e2, int nv) {
-        if (x == 0) { x = v; ex = e2; return true; }
+        if (x == 0) { x = v; ex = e2; return true; }            // keeps the term's own (low) unit: the sum stays short for long
         const int d = e2 - ex;
         if (d < -8) {                                           // the term lies far below the sum's unit: general routine
             start_at(fp64_add_emulated(int53_scaled_to_fp64(x, ex), int53_scaled_to_fp64(v, e2)));
             return false;
         }
         int64_t t;
-        int e;
+        int e = ex;
         if (nv + d <= 62) {                                     // |x| << 8 and |v| << d both stay below 2^62
-            const int left_x = d < 0 ? -d : 0, left_v = d < 0 ? 0 : d;
-            t = (int64_t)(((uint64_t)x << left_x) + ((uint64_t)v << left_v));
-            e = d < 0 ? e2 : ex;
+            if (d >= 0) {                                       // the usual case: the term's unit is not below the sum's
+                t = (int64_t)((uint64_t)x + ((uint64_t)v << d));
+            } else {
+                t = (int64_t)(((uint64_t)x << -d) + (uint64_t)v);
+                e = e2;
+            }
         } else {
             // The term towers over the sum: bring the term's leading bit to position 61 and the sum down to that unit,
             // by r >= 1 bits; what the sum loses is kept as a set lowest bit.  The result then has at least 60 bits,
@@ -194,12 +197,13 @@ struct RoundedSum {
             t = (int64_t)(((uint64_t)v << up) + ((xs ^ sx) - sx));
             e = e2 - up;
         }
-        const uint64_t st = (uint64_t)(t >> 63);
-        const uint64_t a = ((uint64_t)t ^ st) - st;             // |t|
-        const int drop = 11 - clz64(a | 1);                     // bits beyond 53
+        // Round t to 53 significant bits, ties to even, on the two's-complement number itself.  The bit count is
+        // taken from t with its bits flipped if negative (|t| - 1): that is the bit count of |t| except for a negative
+        // power of two, which then keeps one bit more -- it is exact either way and stays within |x| <= 2^53.
+        const uint64_t flipped = (uint64_t)(t ^ (t >> 63));
+        const int drop = 11 - clz64(flipped | 1);               // bits beyond 53
         if (drop > 0) {
-            const uint64_t q = (a + ((1ull << (drop - 1)) - 1) + ((a >> drop) & 1)) >> drop;      // ties to even; may reach 2^53
-            x = (int64_t)((q ^ st) - st);
+            x = (t + (((int64_t)1 << (drop - 1)) - 1) + ((t >> drop) & 1)) >> drop;      // may reach +-2^53
             ex = e + drop;
         } else {
             x = t;

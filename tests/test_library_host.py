@@ -251,6 +251,11 @@ def test_product_rounded_sum_on_host_equals_chain_of_fpu_additions(host_emu):
     # a sum that rounds up to a power of two (2^54 - 1 -> 2^54: the integer significand reaches 2^53) and goes on
     v[1], e2[1] = 0, 0
     v[1, :4], e2[1, :4] = [(1 << 52) - 1, 3, 1, -5], [2, 0, 0, 1]
+    # the same with the signs turned, and a sum that hits a negative power of two exactly (-2^53, then 1 is added twice)
+    v[2], e2[2] = 0, 0
+    v[2, :4], e2[2, :4] = [-((1 << 52) - 1), -3, -1, 5], [2, 0, 0, 1]
+    v[4], e2[4] = 0, 0
+    v[4, :4], e2[4, :4] = [-(1 << 51), -(1 << 51), 1, 1], [1, 1, 0, 0]
     start = np.zeros(n_seq, dtype=np.float64)
     start[::7] = _rnd(rng, start[::7].size, -40, 40)                                          # continued block sums
     out = np.empty(n_seq, dtype=np.uint64)
