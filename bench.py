@@ -17,9 +17,9 @@ region (as in the paper's Section 5.1).  Prints ONE JSON line:
                    at the full inner dimension), in the same unit; the same leg checks the device result
                    bit for bit against the oracle on that sample and reports the error against the exact
                    product on 4096 entries next to a native FP64 GEMM on the same entries
-  other_configs    short runs of the other benchmark configurations that fit the default run (the small case, the
-                   4096^3 slice-count sweep, the two rectangular cases, and the metric workload with FP6 and INT8
-                   slices): time, effective TFLOP/s, GEMM fraction of peak, bit parity with the oracle on a sample
+  other_configs    short runs of the other benchmark configurations (the small case, the 4096^3 slice-count sweep, the
+                   two rectangular cases, the 16384^3 FP8 / k-blocked FP16 comparison, and the metric workload with FP6
+                   and INT8 slices): time, effective TFLOP/s, GEMM fraction of peak, bit parity with the oracle on a sample
 """
 from __future__ import annotations
 
@@ -308,6 +308,12 @@ def main():
         c2cfg = dict(inputs.CONFIGS["c2_4096_fp8_hw"])
         for s2 in range(4, inputs.NUM_SLICES["c2_4096_fp8_hw"] + 1):
             others.append(short_run("c2_4096_fp8_hw", c2cfg, s2, cache, steps=3, sample=32))
+        cache.clear()
+        torch.cuda.empty_cache()
+        # the 16384^3 comparison of unblocked FP8 with k-blocked FP16 slices (one pair of inputs serves the three)
+        for name in ("c4_16384_fp8", "c4_16384_fp16_kb4096", "c4_16384_fp16_kb1024"):
+            others.append(short_run(name, dict(inputs.CONFIGS[name]), inputs.NUM_SLICES[name], cache, steps=2, sample=32))
+        cache.clear()
         out["other_configs"] = others
     print(json.dumps(out))
 
