@@ -130,6 +130,27 @@ def test_split_is_bit_exact(fmt, rows, k, k_block, s, phi, is_B):
             assert np.array_equal(got_codes[t][p], ref_codes[t][p]), (t, p)
 
 
+def _random_split_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(count):
+        fmt = ["fp8", "fp6", "fp6_e3m2", "int8", "fp16"][int(rng.integers(0, 5))]
+        rows = int(rng.integers(1, 600))
+        k = int(rng.choice([int(rng.integers(1, 200)), int(rng.integers(200, 5000)), int(rng.integers(5000, 20000))]))
+        kb = [0, int(rng.integers(1, k + 1))][int(rng.integers(0, 2))]
+        if fmt == "fp16" and (kb or k) > 16384:
+            kb = 4096                                    # the longest FP16 block with an exact FP32 window is 16384 (b = 5)
+        cases.append((fmt, rows, k, kb, int(rng.integers(1, 20)), float(rng.choice([0.5, 2.0, 4.0, 8.0])), int(rng.integers(0, 2))))
+    return cases
+
+
+@pytest.mark.parametrize("fmt,rows,k,k_block,s,phi,is_B", _random_split_cases(36, seed=99))
+def test_split_of_random_shapes_is_bit_exact(fmt, rows, k, k_block, s, phi, is_B):
+    """Seeded random vector counts, lengths (up to blocks that go to the streaming kernel), block lengths, slice counts
+    and value ranges, all formats: codes and exponents bit-identical to the oracle."""
+    test_split_is_bit_exact(fmt, rows, k, k_block, s, phi, is_B)
+
+
 @pytest.mark.parametrize("fmt,k,k_block,s", [("fp8", 64, 0, 9), ("fp8", 4096, 0, 12), ("fp6", 777, 300, 9), ("fp6_e3m2", 64, 0, 12),
                                              ("int8", 1000, 0, 8), ("fp16", 200, 0, 6), ("fp16", 64, 0, 5), ("fp16", 16, 0, 5),
                                              ("fp16", 1024, 0, 7), ("fp8", 40000, 0, 9)])
